@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the WP-SGD hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic workload that is already resident
+in HBM: k SGD chains (wpsgd_run_chains), the weights of Eq. 6 (wpsgd_weights) and the weighted
+model average (wpsgd_combine).  The metric is SGD sample-updates per second over all chains.
+
+Prints ONE JSON line.  Besides the throughput it carries
+  roofline      achieved algorithmic HBM bandwidth of the chain kernel (bytes a sample-update must
+                move x sample-updates per launch / mean launch duration from HIP events recorded
+                on the launch stream inside the timed region) against the 8 TB/s peak;
+  cpu_baseline  the fp64 CPU oracle timed on this machine's host cores on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def kernel_source_digest() -> str:
+    """Digest of the kernel sources; counter-measured traffic is only quoted for the sources it
+    was measured on."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1708_04801_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as fh:
+            h.update(name.encode())
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per chain-kernel launch from the committed counter summary, or None when the
+    kernels have changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        rec = json.load(fh).get(workload)
+    if not rec or rec.get("kernel_source_digest") != kernel_source_digest():
+        return None
+    return rec.get("hbm_bytes_per_launch")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="dense_logistic",
+                    choices=["tiny_hinge", "dense_logistic", "sparse_hinge", "many_chains", "wide_bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--threads", type=int, default=0)
+    ap.add_argument("--block-steps", type=int, default=0)
+    ap.add_argument("--prefetch", type=int, default=0)
+    ap.add_argument("--state-in-hbm", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 "
+              "(chains shard across GPUs with one all-reduce, which is not part of this build)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1708_04801_amd import api
+    from paper_1708_04801_amd import workloads as wl
+
+    api.load()          # raises if the HIP library is missing: there is no fallback
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    t_gen = time.time()
+    w = wl.FULL[args.workload]()
+    t_gen = time.time() - t_gen
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    k, d = w.k, w.d
+    plan = None
+    if args.threads or args.block_steps or args.prefetch or args.state_in_hbm:
+        plan = {"threads": args.threads, "block_steps": args.block_steps, "prefetch": args.prefetch,
+                "state_in_hbm": args.state_in_hbm}
+    desc = api.wpsgd_describe_plan(X, k, w.loss, plan)
+    W = torch.empty((k, d), dtype=torch.float32, device="cuda")
+    v = torch.empty(d, dtype=torch.float32, device="cuda")
+    ws_chain = torch.empty(max(256, api.wpsgd_run_chains_workspace(X, k, w.loss, plan)), dtype=torch.uint8,
+                           device="cuda")
+    ws_comb = torch.empty(max(256, api.wpsgd_combine_workspace(k, d)), dtype=torch.uint8, device="cuda")
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record()
+        api.wpsgd_run_chains(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed, W=W, workspace=ws_chain, plan=plan)
+        if ev is not None:
+            ev[1].record()
+        a = api.wpsgd_weights(w.n_steps, w.eta, w.lam)
+        api.wpsgd_combine(W, a, w_out=v, workspace=ws_comb)
+        if ev is not None:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    total_updates = int(w.n_steps.sum())
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    chain_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    combine_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    # algorithmic bytes of one sample-update: the stored row plus its 4-byte label; CSR adds the
+    # two row offsets and the gather + scatter of the touched model entries (4 bytes each way)
+    if w.is_csr:
+        nnz = w.vals.size / w.m
+        bytes_per_update = nnz * 8 + 16 + 4 + nnz * 8
+    else:
+        bytes_per_update = w.row_bytes() + 4
+    algo_bytes = bytes_per_update * total_updates
+    achieved = algo_bytes / (chain_ms * 1e-3) / 1e9
+    traffic = measured_traffic(args.workload) if plan is None else None
+
+    out = {
+        "metric": "SGD sample-updates/sec (all chains)",
+        "value": total_updates / (ms_per_step * 1e-3),
+        "unit": "sample-updates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.loss == wl.LOGISTIC else "f64",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "m": w.m, "d": d, "k": k, "sample_updates_per_step": total_updates,
+                   "storage": "csr" if w.is_csr else ("bf16" if w.is_bf16 else "f32"),
+                   "loss": "hinge" if w.loss == wl.HINGE else "logistic", "kernel": desc,
+                   "imbalance_mean_over_max": float(w.n_steps.mean() / max(1, w.n_steps.max()))},
+        "roofline": {"bound": "hbm", "kernel": "chain kernel (wpsgd_run_chains)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "bytes_per_sample_update": bytes_per_update,
+                     "kernel_ms": chain_ms, "combine_ms": combine_ms},
+        "data_generation_s": t_gen,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        Xo = orc.CSR(w.row_ptr, w.col_idx, w.vals, w.d) if w.is_csr else orc.Dense(w.dense)
+        cores = min(k, len(os.sched_getaffinity(0)))
+        n_cpu, sample = w.n_steps, "the whole workload, all chains in full"
+        csr_mode, mode_name = orc.PLAIN, "plain"
+        if args.workload == "sparse_hinge":
+            csr_mode, mode_name = orc.LAZY, "scalar-scale (the literal shrink touches 2^20 doubles a step)"
+        elif args.workload == "wide_bf16":
+            n_cpu = np.minimum(w.n_steps, 1000)
+            sample = "every chain cut to its first 1000 steps"
+        tc = time.perf_counter()
+        Wo, _ = orc.run_chains(Xo, w.y, n_cpu, w.eta, w.lam, w.loss, w.seed, csr_mode=csr_mode, threads=cores)
+        a = orc.weights(n_cpu, w.eta, w.lam)
+        vo = orc.combine(Wo, a)
+        tc = time.perf_counter() - tc
+        out["cpu_baseline"] = {"value": float(n_cpu.sum()) / tc, "unit": "sample-updates/s", "cores": cores,
+                               "kind": "oracle", "sample": sample, "mode": mode_name, "seconds": tc}
+        if n_cpu is w.n_steps:
+            vg = v.cpu().numpy().astype(np.float64)
+            out["parity_rel_l2"] = float(np.linalg.norm(vg - vo) / max(np.linalg.norm(vo), 1e-300))
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,139 @@
+/*
+ * wpsgd.h -- C ABI of the WP-SGD hot path on AMD MI355X (gfx950).
+ *
+ * The library runs k independent sequential SGD chains of unequal length on an
+ * L2-regularised linear loss and then forms one weighted model average, as in
+ * Algorithm 1 ("WP-SGD") of arXiv 1708.04801.
+ *
+ * Conventions for every entry point
+ *   - Return value: WPSGD_OK (0) or a negative wpsgd_status.  Nothing throws.
+ *   - "DEVICE" pointers are HIP device addresses on the current device, owned by
+ *     the caller; "HOST" pointers are ordinary host memory.  The library never
+ *     frees or keeps a caller pointer past the call.  (HOST inputs are copied
+ *     before the call returns.)
+ *   - GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and is NOT synchronised: device outputs are complete
+ *     when the stream reaches that point.  HOST outputs are complete on return.
+ *   - Step counts: n_steps[i] is the number of SGD steps chain i runs.  In the
+ *     paper's notation the fastest node consumes t = max_i n_steps[i] samples
+ *     and node i is T_i = t - n_steps[i] steps behind it (Algorithm 1; Table I).
+ *   - The library allocates no device memory; scratch space is a caller-provided
+ *     workspace whose size the *_workspace functions report.
+ */
+#ifndef WPSGD_H
+#define WPSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    WPSGD_OK = 0,
+    WPSGD_INVALID_ARG = -1,        /* NULL pointer, size out of range, bad enum, eta*lambda >= 1 ... */
+    WPSGD_HIP_ERROR = -2,          /* a HIP call failed; see wpsgd_last_hip_error()                  */
+    WPSGD_WORKSPACE_TOO_SMALL = -3,
+    WPSGD_UNSUPPORTED = -4         /* a forced plan that no kernel implements                        */
+} wpsgd_status;
+
+/* L(x, y, yhat) of Eq. 4, a convex function of yhat = w.x:
+ *   hinge    max(0, 1 - y*yhat)      slope -y where y*yhat < 1, 0 elsewhere (0 at the kink)
+ *   logistic log(1 + exp(-y*yhat))   slope -y / (1 + exp(y*yhat))                            */
+typedef enum { WPSGD_HINGE = 0, WPSGD_LOGISTIC = 1 } wpsgd_loss;
+
+/* Storage type of dense rows.  bfloat16 values are widened exactly to fp32 on load. */
+typedef enum { WPSGD_F32 = 0, WPSGD_BF16 = 1 } wpsgd_dtype;
+
+/* The data set {x^1..x^m} of Eq. 3, one example per row.  Exactly one of `dense`
+ * and the CSR triple is non-NULL.  All pointers are DEVICE pointers.            */
+typedef struct wpsgd_matrix {
+    int64_t m;                 /* rows (examples), 1 <= m < 2^32                             */
+    int64_t d;                 /* columns (model dimension), d >= 1                          */
+    const void *dense;         /* row-major m x d, element (j,c) at dense[j*ld + c]; or NULL */
+    int64_t ld;                /* row stride in elements, ld >= d (ignored for CSR)          */
+    wpsgd_dtype dtype;         /* storage of `dense` (CSR values are always fp32)            */
+    const int64_t *row_ptr;    /* CSR: m+1 offsets, row j is [row_ptr[j], row_ptr[j+1])      */
+    const int32_t *col_idx;    /* CSR: column of each entry, strictly ascending in a row, < d */
+    const float *vals;         /* CSR: value of each entry                                   */
+} wpsgd_matrix;
+
+/* Optional kernel plan for wpsgd_run_chains; zero in a field means "choose for me".
+ * Used by the tests and the tuner to reach every kernel variant at any size.      */
+typedef struct wpsgd_plan {
+    int threads;         /* workgroup size of a chain: 64, 256, 512 or 1024                      */
+    int block_steps;     /* SGD steps folded into one reduction round: 1, 2, 4 or 8             */
+    int prefetch;        /* rounds of sample rows kept in flight ahead of the one being consumed */
+    int state_in_hbm;    /* 1: keep the model vector in the workspace (HBM) instead of registers */
+} wpsgd_plan;
+
+/* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----
+ *
+ * Chain i (i = 0..k-1) starts from w = 0 and performs n_steps[i] updates
+ *     w <- (1 - eta*lambda) * w  -  eta * dL/dyhat(y_j, w.x_j) * x_j
+ * where j is the row its own sample stream names at that step (see
+ * wpsgd_sample_indices).  The result of chain i is written to W[i*d .. i*d+d).
+ *
+ *   X, y        DEVICE; y holds m labels, each -1 or +1
+ *   k           number of chains, 1 <= k <= 2^31-1
+ *   n_steps     HOST, k entries, each >= 0 (0: the chain does nothing, its row of W is 0)
+ *   eta, lambda eta > 0, lambda >= 0, eta*lambda < 1
+ *   seed        key of the sample stream
+ *   W           DEVICE out, k x d row-major fp32
+ *   workspace   DEVICE scratch of at least wpsgd_run_chains_workspace(...) bytes, 256-byte
+ *               aligned; contents on entry are ignored, contents on exit are unspecified
+ *   plan        NULL or a forced kernel plan
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED (forced plan), HIP_ERROR.
+ * Two calls that share a workspace must be ordered on one stream.                        */
+size_t wpsgd_run_chains_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss,
+                                  const wpsgd_plan *plan);
+int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
+                     double eta, double lambda, wpsgd_loss loss, uint64_t seed,
+                     float *W, void *workspace, size_t workspace_bytes,
+                     const wpsgd_plan *plan, void *stream);
+
+/* ---- weights (Eq. 6; Eq. 8 for a chosen contraction rate r) ----
+ *   a[i] = rate^{T_i} / sum_j rate^{T_j},  T_i = max_j n_steps[j] - n_steps[i],
+ *   rate = 1 - eta*lambda (wpsgd_weights) or r in (0, 1] (wpsgd_weights_rate).
+ * Pure host code, fp64.  a is HOST out, k entries.  Equal step counts give exactly 1/k
+ * (the plain average of SimuParallel SGD, Algorithm 2).                                   */
+int wpsgd_weights(int k, const int64_t *n_steps, double eta, double lambda, double *a);
+int wpsgd_weights_rate(int k, const int64_t *n_steps, double rate, double *a);
+
+/* Benefit condition of Eq. 7 / Eq. 9 (Corollary 3 / 4): *margin receives
+ * 2*sum_i rate^{T_i} - (sqrt(k) + k); positive means the condition holds.  HOST only.  */
+int wpsgd_benefit_margin(int k, const int64_t *n_steps, double rate, double *margin);
+
+/* ---- weighted model average (Algorithm 1, the aggregation line; Lemma 3) ----
+ *   w_out[c] = sum_{i=0}^{k-1} a[i] * W[i*d + c],  accumulated in fp64, rounded once to fp32.
+ *   W       DEVICE k x d row-major fp32        a      HOST, k entries
+ *   w_out   DEVICE out, d entries fp32
+ *   workspace DEVICE scratch of at least wpsgd_combine_workspace(k, d) bytes, 256-byte aligned */
+size_t wpsgd_combine_workspace(int k, int64_t d);
+int wpsgd_combine(const float *W, const double *a, int k, int64_t d, float *w_out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- sample stream (stands for "shuffle, then take the n-th example", Algorithm 1) ----
+ * Row visited by chain `chain` at step n (0-based):
+ *   (r0,..) = Philox4x32-10(counter = (n mod 2^32, n div 2^32, chain, 0),
+ *                           key = (seed mod 2^32, seed div 2^32));   j = floor(r0 * m / 2^32).
+ * Writes rows for steps n0 .. n0+count-1.  The HOST variant runs the generator on the CPU;
+ * the DEVICE variant runs the same generator the chain kernels use and writes to DEVICE memory. */
+int wpsgd_sample_indices(uint64_t seed, int chain, int64_t n0, int64_t count, int64_t m,
+                         int64_t *out_host);
+int wpsgd_sample_indices_device(uint64_t seed, int chain, int64_t n0, int64_t count, int64_t m,
+                                int64_t *out_device, void *stream);
+
+/* ---- diagnostics ---- */
+const char *wpsgd_strerror(int status);
+int wpsgd_last_hip_error(void);           /* hipError_t of the last failed HIP call on this thread */
+/* Writes a short description of the kernel the given problem would run (for logs and the
+ * tuner), e.g. "dense_reg f32 logistic nt=256 ept=16 vec=4 B=4 P=2".  HOST.                */
+int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *plan,
+                        char *buf, size_t buf_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WPSGD_H */

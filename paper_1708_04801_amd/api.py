@@ -1,0 +1,254 @@
+"""ctypes binding of libwpsgd.so: same names as the C ABI in include/wpsgd.h.
+
+Argument marshalling only -- every step of the path runs in the HIP library.  PyTorch is
+used for device memory (tensors) and for the current HIP stream; nothing here computes.
+There is no CPU fallback: if the library is missing or cannot be loaded, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libwpsgd.so")
+
+HINGE, LOGISTIC = 0, 1
+F32, BF16 = 0, 1
+OK, INVALID_ARG, HIP_ERROR, WORKSPACE_TOO_SMALL, UNSUPPORTED = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "wpsgd_run_chains_workspace", "wpsgd_run_chains", "wpsgd_weights", "wpsgd_weights_rate",
+    "wpsgd_benefit_margin", "wpsgd_combine_workspace", "wpsgd_combine", "wpsgd_sample_indices",
+    "wpsgd_sample_indices_device", "wpsgd_strerror", "wpsgd_last_hip_error", "wpsgd_describe_plan",
+]
+
+
+class _CMatrix(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int64), ("d", ctypes.c_int64), ("dense", ctypes.c_void_p),
+                ("ld", ctypes.c_int64), ("dtype", ctypes.c_int), ("row_ptr", ctypes.c_void_p),
+                ("col_idx", ctypes.c_void_p), ("vals", ctypes.c_void_p)]
+
+
+class _CPlan(ctypes.Structure):
+    _fields_ = [("threads", ctypes.c_int), ("block_steps", ctypes.c_int),
+                ("prefetch", ctypes.c_int), ("state_in_hbm", ctypes.c_int)]
+
+
+class WpsgdError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        msg = load().wpsgd_strerror(status).decode()
+        if status == HIP_ERROR:
+            msg += f" [hipError {load().wpsgd_last_hip_error()}]"
+        super().__init__(f"{what}: {msg} (status {status})")
+
+
+_lib = None
+
+
+def load():
+    """Loads libwpsgd.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1708_04801_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    i64, f64, ci, u64, vp, sz = (ctypes.c_int64, ctypes.c_double, ctypes.c_int, ctypes.c_uint64,
+                                 ctypes.c_void_p, ctypes.c_size_t)
+    pm, pp = ctypes.POINTER(_CMatrix), ctypes.POINTER(_CPlan)
+    L.wpsgd_run_chains_workspace.argtypes = [pm, ci, ci, pp]
+    L.wpsgd_run_chains_workspace.restype = sz
+    L.wpsgd_run_chains.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, sz, pp, vp]
+    L.wpsgd_weights.argtypes = [ci, vp, f64, f64, vp]
+    L.wpsgd_weights_rate.argtypes = [ci, vp, f64, vp]
+    L.wpsgd_benefit_margin.argtypes = [ci, vp, f64, vp]
+    L.wpsgd_combine_workspace.argtypes = [ci, i64]
+    L.wpsgd_combine_workspace.restype = sz
+    L.wpsgd_combine.argtypes = [vp, vp, ci, i64, vp, vp, sz, vp]
+    L.wpsgd_sample_indices.argtypes = [u64, ci, i64, i64, i64, vp]
+    L.wpsgd_sample_indices_device.argtypes = [u64, ci, i64, i64, i64, vp, vp]
+    L.wpsgd_strerror.argtypes = [ci]
+    L.wpsgd_strerror.restype = ctypes.c_char_p
+    L.wpsgd_last_hip_error.argtypes = []
+    L.wpsgd_describe_plan.argtypes = [pm, ci, ci, pp, ctypes.c_char_p, sz]
+    _lib = L
+    return L
+
+
+@dataclass
+class Matrix:
+    """Device-resident data set.  dense: float32 [m,d] tensor, or int16/uint16/bfloat16 [m,d]
+    holding bfloat16 values; or CSR with int64 row_ptr, int32 col_idx, float32 vals."""
+    m: int
+    d: int
+    dense: Optional[torch.Tensor] = None
+    row_ptr: Optional[torch.Tensor] = None
+    col_idx: Optional[torch.Tensor] = None
+    vals: Optional[torch.Tensor] = None
+
+    def c_struct(self) -> _CMatrix:
+        c = _CMatrix()
+        c.m, c.d = int(self.m), int(self.d)
+        if self.dense is not None:
+            t = self.dense
+            assert t.is_cuda and t.dim() == 2 and t.stride(1) == 1
+            c.dense = t.data_ptr()
+            c.ld = t.stride(0)
+            c.dtype = F32 if t.dtype == torch.float32 else BF16
+            assert t.dtype in (torch.float32, torch.bfloat16, torch.int16, torch.uint16)
+        else:
+            assert self.row_ptr.dtype == torch.int64 and self.col_idx.dtype == torch.int32
+            assert self.vals.dtype == torch.float32 and self.row_ptr.is_cuda
+            c.row_ptr, c.col_idx, c.vals = (self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+                                            self.vals.data_ptr())
+        return c
+
+
+def matrix_from_workload(w, device="cuda") -> Matrix:
+    """Uploads a generated workload's data set to the GPU."""
+    if w.dense is not None:
+        host = torch.from_numpy(w.dense.view(np.int16) if w.dense.dtype == np.uint16 else w.dense)
+        dev = host.to(device)
+        if w.dense.dtype == np.uint16:
+            dev = dev.view(torch.bfloat16)
+        return Matrix(w.m, w.d, dense=dev)
+    return Matrix(w.m, w.d, row_ptr=torch.from_numpy(w.row_ptr).to(device),
+                  col_idx=torch.from_numpy(w.col_idx).to(device),
+                  vals=torch.from_numpy(w.vals).to(device))
+
+
+def _plan(plan):
+    if plan is None:
+        return None
+    p = _CPlan()
+    p.threads = int(plan.get("threads", 0))
+    p.block_steps = int(plan.get("block_steps", 0))
+    p.prefetch = int(plan.get("prefetch", 0))
+    p.state_in_hbm = int(plan.get("state_in_hbm", 0))
+    return ctypes.byref(p)
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _steps(n_steps):
+    return np.ascontiguousarray(np.asarray(n_steps), dtype=np.int64)
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def wpsgd_describe_plan(X: Matrix, k, loss, plan=None) -> str:
+    buf = ctypes.create_string_buffer(256)
+    cm = X.c_struct()
+    rc = load().wpsgd_describe_plan(ctypes.byref(cm), int(k), int(loss), _plan(plan), buf, 256)
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_describe_plan")
+    return buf.value.decode()
+
+
+def wpsgd_run_chains_workspace(X: Matrix, k, loss, plan=None) -> int:
+    cm = X.c_struct()
+    return int(load().wpsgd_run_chains_workspace(ctypes.byref(cm), int(k), int(loss), _plan(plan)))
+
+
+def wpsgd_run_chains(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
+                     W: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     plan=None, stream=None) -> torch.Tensor:
+    """Runs the k chains; returns W (k x d float32 on the GPU).  Asynchronous on the stream."""
+    n = _steps(n_steps)
+    k = int(n.size)
+    dev = y.device
+    assert y.is_cuda and y.dtype == torch.float32 and y.numel() == X.m
+    if W is None:
+        W = torch.empty((k, X.d), dtype=torch.float32, device=dev)
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.shape == (k, X.d)
+    cm = X.c_struct()
+    pl = _plan(plan)
+    if workspace is None:
+        need = load().wpsgd_run_chains_workspace(ctypes.byref(cm), k, int(loss), pl)
+        workspace = _workspace(need, dev)
+    rc = load().wpsgd_run_chains(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, float(eta),
+                                 float(lam), int(loss), int(seed), W.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), pl, _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_run_chains")
+    return W
+
+
+def wpsgd_weights(n_steps, eta, lam) -> np.ndarray:
+    n = _steps(n_steps)
+    a = np.zeros(n.size, dtype=np.float64)
+    rc = load().wpsgd_weights(int(n.size), n.ctypes.data, float(eta), float(lam), a.ctypes.data)
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_weights")
+    return a
+
+
+def wpsgd_weights_rate(n_steps, rate) -> np.ndarray:
+    n = _steps(n_steps)
+    a = np.zeros(n.size, dtype=np.float64)
+    rc = load().wpsgd_weights_rate(int(n.size), n.ctypes.data, float(rate), a.ctypes.data)
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_weights_rate")
+    return a
+
+
+def wpsgd_benefit_margin(n_steps, rate) -> float:
+    n = _steps(n_steps)
+    out = ctypes.c_double(0.0)
+    rc = load().wpsgd_benefit_margin(int(n.size), n.ctypes.data, float(rate),
+                                     ctypes.addressof(out))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_benefit_margin")
+    return out.value
+
+
+def wpsgd_combine_workspace(k, d) -> int:
+    return int(load().wpsgd_combine_workspace(int(k), int(d)))
+
+
+def wpsgd_combine(W: torch.Tensor, a, w_out: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """w_out = sum_i a[i] * W[i,:]; returns w_out (d float32 on the GPU)."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2 and W.is_contiguous()
+    k, d = W.shape
+    a = np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+    assert a.shape == (k,)
+    if w_out is None:
+        w_out = torch.empty(d, dtype=torch.float32, device=W.device)
+    if workspace is None:
+        workspace = _workspace(wpsgd_combine_workspace(k, d), W.device)
+    rc = load().wpsgd_combine(W.data_ptr(), a.ctypes.data, k, d, w_out.data_ptr(),
+                              workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_combine")
+    return w_out
+
+
+def wpsgd_sample_indices(seed, chain, n0, count, m) -> np.ndarray:
+    out = np.zeros(max(int(count), 0), dtype=np.int64)
+    rc = load().wpsgd_sample_indices(int(seed), int(chain), int(n0), int(count), int(m),
+                                     out.ctypes.data)
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_sample_indices")
+    return out
+
+
+def wpsgd_sample_indices_device(seed, chain, n0, count, m, device="cuda", stream=None) -> torch.Tensor:
+    out = torch.empty(max(int(count), 0), dtype=torch.int64, device=device)
+    rc = load().wpsgd_sample_indices_device(int(seed), int(chain), int(n0), int(count), int(m),
+                                            out.data_ptr(), _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_sample_indices_device")
+    return out

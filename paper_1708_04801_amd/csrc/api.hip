@@ -1,0 +1,392 @@
+// The C ABI of libwpsgd (see wpsgd.h): argument checks, the kernel planner, the host-side
+// weights of Eq. 6 / Eq. 8, and the small host->device hand-overs the kernels need.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "device_utils.h"
+#include "internal.h"
+
+namespace wpsgd {
+
+hipError_t dense_reg_dispatch_f32_loss0(Plan &, const ChainArgs *, hipStream_t);
+hipError_t dense_reg_dispatch_f32_loss1(Plan &, const ChainArgs *, hipStream_t);
+hipError_t dense_reg_dispatch_bf16_loss0(Plan &, const ChainArgs *, hipStream_t);
+hipError_t dense_reg_dispatch_bf16_loss1(Plan &, const ChainArgs *, hipStream_t);
+bool dense_reg_shape_f32_loss0(int, int, int);
+bool dense_reg_shape_f32_loss1(int, int, int);
+bool dense_reg_shape_bf16_loss0(int, int, int);
+bool dense_reg_shape_bf16_loss1(int, int, int);
+
+static thread_local int g_last_hip_error = 0;
+
+static int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return WPSGD_HIP_ERROR;
+}
+
+static hipError_t dense_reg_dispatch(Plan &p, const ChainArgs *a, hipStream_t s)
+{
+    if (p.dtype == WPSGD_BF16)
+        return p.loss == WPSGD_HINGE ? dense_reg_dispatch_bf16_loss0(p, a, s)
+                                     : dense_reg_dispatch_bf16_loss1(p, a, s);
+    return p.loss == WPSGD_HINGE ? dense_reg_dispatch_f32_loss0(p, a, s)
+                                 : dense_reg_dispatch_f32_loss1(p, a, s);
+}
+
+static bool dense_reg_shape(int dtype, int loss, int threads, int ept, int vec)
+{
+    if (dtype == WPSGD_BF16)
+        return loss == WPSGD_HINGE ? dense_reg_shape_bf16_loss0(threads, ept, vec)
+                                   : dense_reg_shape_bf16_loss1(threads, ept, vec);
+    return loss == WPSGD_HINGE ? dense_reg_shape_f32_loss0(threads, ept, vec)
+                               : dense_reg_shape_f32_loss1(threads, ept, vec);
+}
+
+static int check_matrix(const wpsgd_matrix *X)
+{
+    if (!X) return WPSGD_INVALID_ARG;
+    if (X->m < 1 || X->m > 0xFFFFFFFFLL || X->d < 1) return WPSGD_INVALID_ARG;
+    const bool has_csr = X->row_ptr || X->col_idx || X->vals;
+    if (X->dense) {
+        if (has_csr) return WPSGD_INVALID_ARG;
+        if (X->ld < X->d) return WPSGD_INVALID_ARG;
+        if (X->dtype != WPSGD_F32 && X->dtype != WPSGD_BF16) return WPSGD_INVALID_ARG;
+    } else {
+        if (!(X->row_ptr && X->col_idx && X->vals)) return WPSGD_INVALID_ARG;
+    }
+    return WPSGD_OK;
+}
+
+// Widest load the rows allow: every row start and every fragment must be 16-byte aligned.
+static int dense_vec(const wpsgd_matrix *X)
+{
+    const int wide = X->dtype == WPSGD_BF16 ? 8 : 4;
+    const bool ok = ((uintptr_t)X->dense % 16 == 0) && (X->ld % wide == 0) && (X->d % wide == 0);
+    return ok ? wide : 1;
+}
+
+// Chooses the kernel family and its parameters.  Dense rows go to the register kernel when
+// some instantiated shape holds d elements, else to the HBM-state kernel.
+static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan *force, Plan *out)
+{
+    Plan p{};
+    p.loss = (int)loss;
+    p.dtype = X->dense ? (int)X->dtype : WPSGD_F32;
+    const size_t state_elem = (loss == WPSGD_HINGE) ? sizeof(double) : sizeof(float);
+    const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0};
+    if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0) return WPSGD_INVALID_ARG;
+
+    if (!X->dense) {
+        if (f.threads && f.threads != kWave) return WPSGD_UNSUPPORTED;
+        if (f.block_steps > 1 || f.prefetch > 1) return WPSGD_UNSUPPORTED;
+        p.family = Family::Csr;
+        p.threads = kWave;
+        p.vec = 1;
+        p.block_steps = 1;
+        p.prefetch = 1;
+        p.state_bytes_per_elem = state_elem;
+        *out = p;
+        return WPSGD_OK;
+    }
+
+    const int wide = dense_vec(X);
+    p.vec = wide;
+    if (!f.state_in_hbm) {
+        static const int kThreads[] = {64, 256, 512, 1024};
+        static const int kEpt[] = {1, 2, 4, 8, 16, 32, 64, 128};
+        // smallest workgroup first, then the smallest fragment that covers d; fragments much
+        // narrower than one wide load use scalar loads so that all lanes carry data
+        for (int nt : kThreads) {
+            if (f.threads && f.threads != nt) continue;
+            for (int ept : kEpt) {
+                if ((int64_t)nt * ept < X->d) continue;
+                int vec = wide;
+                if (wide > 1 && ept * 4 <= wide) vec = 1;
+                if (ept % vec != 0) continue;
+                if (!dense_reg_shape(p.dtype, p.loss, nt, ept, vec)) continue;
+                Plan q = p;
+                q.vec = vec;
+                q.family = Family::DenseReg;
+                q.threads = nt;
+                q.ept = ept;
+                q.block_steps = f.block_steps;
+                q.prefetch = f.prefetch;
+                q.state_bytes_per_elem = 0;
+                if (dense_reg_dispatch(q, nullptr, nullptr) == hipSuccess) {
+                    *out = q;
+                    return WPSGD_OK;
+                }
+            }
+        }
+        if (f.threads || f.block_steps || f.prefetch) return WPSGD_UNSUPPORTED;
+    }
+    p.family = Family::DenseMem;
+    p.threads = f.threads ? f.threads : (X->d >= 16384 ? 1024 : 256);
+    if (p.threads != 256 && p.threads != 1024) return WPSGD_UNSUPPORTED;
+    if (f.block_steps > 1 || f.prefetch > 1) return WPSGD_UNSUPPORTED;
+    p.block_steps = 1;
+    p.prefetch = 1;
+    p.state_bytes_per_elem = state_elem;
+    *out = p;
+    return WPSGD_OK;
+}
+
+static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+static size_t header_bytes(int k)
+{
+    return align256((size_t)k * sizeof(int32_t)) + align256((size_t)k * sizeof(int64_t));
+}
+
+// Frees a host staging buffer once the stream has consumed it.
+static void free_staging(void *p) { std::free(p); }
+
+static int upload(void *dst, const void *src, size_t bytes, hipStream_t s)
+{
+    // The source must outlive the asynchronous copy: stage it in a heap block that a host
+    // callback on the same stream releases.
+    void *stage = std::malloc(bytes);
+    if (!stage) return WPSGD_INVALID_ARG;
+    std::memcpy(stage, src, bytes);
+    hipError_t e = hipMemcpyAsync(dst, stage, bytes, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) {
+        std::free(stage);
+        return hip_fail(e);
+    }
+    e = hipLaunchHostFunc(s, free_staging, stage);
+    if (e != hipSuccess) {
+        (void)hipStreamSynchronize(s);
+        std::free(stage);
+        return hip_fail(e);
+    }
+    return WPSGD_OK;
+}
+
+static int check_steps(int k, const int64_t *n_steps)
+{
+    if (k < 1 || !n_steps) return WPSGD_INVALID_ARG;
+    for (int i = 0; i < k; ++i)
+        if (n_steps[i] < 0) return WPSGD_INVALID_ARG;
+    return WPSGD_OK;
+}
+
+static const char *family_name(Family f)
+{
+    switch (f) {
+    case Family::DenseReg: return "dense_reg";
+    case Family::DenseMem: return "dense_mem";
+    default: return "csr";
+    }
+}
+
+}  // namespace wpsgd
+
+using namespace wpsgd;
+
+extern "C" {
+
+size_t wpsgd_run_chains_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *plan)
+{
+    if (check_matrix(X) != WPSGD_OK || k < 1) return 0;
+    if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return 0;
+    Plan p;
+    if (resolve_plan(X, loss, plan, &p) != WPSGD_OK) return 0;
+    return header_bytes(k) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
+}
+
+int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *plan,
+                        char *buf, size_t buf_bytes)
+{
+    if (!buf || buf_bytes == 0 || k < 1) return WPSGD_INVALID_ARG;
+    int rc = check_matrix(X);
+    if (rc != WPSGD_OK) return rc;
+    if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
+    Plan p;
+    rc = resolve_plan(X, loss, plan, &p);
+    if (rc != WPSGD_OK) return rc;
+    std::snprintf(buf, buf_bytes, "%s %s %s nt=%d ept=%d vec=%d B=%d P=%d state=%s",
+                  family_name(p.family), p.dtype == WPSGD_BF16 ? "bf16" : "f32",
+                  p.loss == WPSGD_HINGE ? "hinge" : "logistic", p.threads, p.ept, p.vec,
+                  p.block_steps, p.prefetch,
+                  p.state_bytes_per_elem == 0 ? "registers" : (p.state_bytes_per_elem == 8 ? "hbm-f64" : "hbm-f32"));
+    return WPSGD_OK;
+}
+
+int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
+                     double eta, double lambda, wpsgd_loss loss, uint64_t seed, float *W,
+                     void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream)
+{
+    int rc = check_matrix(X);
+    if (rc != WPSGD_OK) return rc;
+    if (!y || !W) return WPSGD_INVALID_ARG;
+    rc = check_steps(k, n_steps);
+    if (rc != WPSGD_OK) return rc;
+    if (!(eta > 0.0) || !(lambda >= 0.0) || !(eta * lambda < 1.0)) return WPSGD_INVALID_ARG;
+    if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
+    Plan p;
+    rc = resolve_plan(X, loss, plan, &p);
+    if (rc != WPSGD_OK) return rc;
+    const size_t need = header_bytes(k) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
+    if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
+    if (workspace_bytes < need) return WPSGD_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    // longest chain first (stable, so equal lengths keep their order)
+    std::vector<int32_t> order(k);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t x, int32_t z) { return n_steps[x] > n_steps[z]; });
+    std::vector<int64_t> sorted_steps(k);
+    for (int b = 0; b < k; ++b) sorted_steps[b] = n_steps[order[b]];
+
+    char *ws = static_cast<char *>(workspace);
+    int32_t *order_dev = reinterpret_cast<int32_t *>(ws);
+    int64_t *steps_dev = reinterpret_cast<int64_t *>(ws + align256((size_t)k * sizeof(int32_t)));
+    void *state_dev = ws + header_bytes(k);
+    rc = upload(order_dev, order.data(), (size_t)k * sizeof(int32_t), s);
+    if (rc != WPSGD_OK) return rc;
+    rc = upload(steps_dev, sorted_steps.data(), (size_t)k * sizeof(int64_t), s);
+    if (rc != WPSGD_OK) return rc;
+
+    ChainArgs a{};
+    a.dense = X->dense;
+    a.ld = X->ld;
+    a.row_ptr = X->row_ptr;
+    a.col_idx = X->col_idx;
+    a.vals = X->vals;
+    a.y = y;
+    a.m = X->m;
+    a.d = X->d;
+    a.k = k;
+    a.order = order_dev;
+    a.nsteps = steps_dev;
+    a.eta = eta;
+    a.rho = 1.0 - eta * lambda;
+    a.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);
+    a.seed_hi = (uint32_t)(seed >> 32);
+    a.W = W;
+    a.state = state_dev;
+
+    hipError_t e;
+    switch (p.family) {
+    case Family::DenseReg: e = dense_reg_dispatch(p, &a, s); break;
+    case Family::DenseMem: e = launch_dense_mem(p, a, s); break;
+    default: e = launch_csr(p, a, s); break;
+    }
+    if (e == hipErrorInvalidValue) return WPSGD_UNSUPPORTED;
+    return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
+int wpsgd_weights_rate(int k, const int64_t *n_steps, double rate, double *a)
+{
+    int rc = check_steps(k, n_steps);
+    if (rc != WPSGD_OK) return rc;
+    if (!a || !(rate > 0.0) || !(rate <= 1.0)) return WPSGD_INVALID_ARG;
+    int64_t t = 0;
+    for (int i = 0; i < k; ++i) t = std::max(t, n_steps[i]);
+    // rate^T = exp(T * log(rate)); the fastest chain has T = 0, so the sum is at least 1
+    const double log_rate = std::log(rate);
+    double total = 0.0;
+    for (int i = 0; i < k; ++i) {
+        a[i] = std::exp((double)(t - n_steps[i]) * log_rate);
+        total += a[i];
+    }
+    for (int i = 0; i < k; ++i) a[i] /= total;
+    return WPSGD_OK;
+}
+
+int wpsgd_weights(int k, const int64_t *n_steps, double eta, double lambda, double *a)
+{
+    if (!(eta > 0.0) || !(lambda >= 0.0) || !(eta * lambda < 1.0)) return WPSGD_INVALID_ARG;
+    int rc = check_steps(k, n_steps);
+    if (rc != WPSGD_OK) return rc;
+    if (!a) return WPSGD_INVALID_ARG;
+    int64_t t = 0;
+    for (int i = 0; i < k; ++i) t = std::max(t, n_steps[i]);
+    const double log_rate = std::log1p(-eta * lambda);    // log(1 - eta*lambda) without cancellation
+    double total = 0.0;
+    for (int i = 0; i < k; ++i) {
+        a[i] = std::exp((double)(t - n_steps[i]) * log_rate);
+        total += a[i];
+    }
+    for (int i = 0; i < k; ++i) a[i] /= total;
+    return WPSGD_OK;
+}
+
+int wpsgd_benefit_margin(int k, const int64_t *n_steps, double rate, double *margin)
+{
+    int rc = check_steps(k, n_steps);
+    if (rc != WPSGD_OK) return rc;
+    if (!margin || !(rate > 0.0) || !(rate <= 1.0)) return WPSGD_INVALID_ARG;
+    int64_t t = 0;
+    for (int i = 0; i < k; ++i) t = std::max(t, n_steps[i]);
+    const double log_rate = std::log(rate);
+    double total = 0.0;
+    for (int i = 0; i < k; ++i) total += std::exp((double)(t - n_steps[i]) * log_rate);
+    *margin = 2.0 * total - (std::sqrt((double)k) + (double)k);
+    return WPSGD_OK;
+}
+
+size_t wpsgd_combine_workspace(int k, int64_t d)
+{
+    (void)d;
+    return k < 1 ? 0 : align256((size_t)k * sizeof(double));
+}
+
+int wpsgd_combine(const float *W, const double *a, int k, int64_t d, float *w_out, void *workspace,
+                  size_t workspace_bytes, void *stream)
+{
+    if (!W || !a || !w_out || k < 1 || d < 1) return WPSGD_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
+    if (workspace_bytes < wpsgd_combine_workspace(k, d)) return WPSGD_WORKSPACE_TOO_SMALL;
+    for (int i = 0; i < k; ++i)
+        if (!std::isfinite(a[i])) return WPSGD_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int rc = upload(workspace, a, (size_t)k * sizeof(double), s);
+    if (rc != WPSGD_OK) return rc;
+    hipError_t e = launch_combine(W, static_cast<const double *>(workspace), k, d, w_out, s);
+    return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
+int wpsgd_sample_indices(uint64_t seed, int chain, int64_t n0, int64_t count, int64_t m,
+                         int64_t *out_host)
+{
+    if (chain < 0 || n0 < 0 || count < 0 || m < 1 || m > 0xFFFFFFFFLL) return WPSGD_INVALID_ARG;
+    if (count > 0 && !out_host) return WPSGD_INVALID_ARG;
+    for (int64_t t = 0; t < count; ++t)
+        out_host[t] = (int64_t)sample_row((uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32),
+                                          (uint32_t)chain, (uint64_t)(n0 + t), (uint32_t)m);
+    return WPSGD_OK;
+}
+
+int wpsgd_sample_indices_device(uint64_t seed, int chain, int64_t n0, int64_t count, int64_t m,
+                                int64_t *out_device, void *stream)
+{
+    if (chain < 0 || n0 < 0 || count < 0 || m < 1 || m > 0xFFFFFFFFLL) return WPSGD_INVALID_ARG;
+    if (count > 0 && !out_device) return WPSGD_INVALID_ARG;
+    hipError_t e = launch_sample_rows((uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32),
+                                      (uint32_t)chain, n0, count, (uint32_t)m, out_device,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
+const char *wpsgd_strerror(int status)
+{
+    switch (status) {
+    case WPSGD_OK: return "ok";
+    case WPSGD_INVALID_ARG: return "invalid argument";
+    case WPSGD_HIP_ERROR: return "HIP call failed (see wpsgd_last_hip_error)";
+    case WPSGD_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case WPSGD_UNSUPPORTED: return "no kernel implements the forced plan";
+    default: return "unknown status";
+    }
+}
+
+int wpsgd_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

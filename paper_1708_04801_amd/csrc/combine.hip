@@ -1,0 +1,145 @@
+// Weighted model average  w_out[c] = sum_i a_i W[i,c]  (the aggregation line of Algorithm 1;
+// Lemma 3) and the device-side view of the sample stream.
+//
+// The average is a pure stream over the k x d matrix W: every column is owned by one thread
+// (four adjacent columns when alignment allows), rows are walked in ascending order with
+// several loads in flight, and the sum is kept in fp64 and rounded once.  When there are too
+// few columns to fill the chip, the rows are split over RS slices of a workgroup whose partial
+// sums are added in slice order through LDS, so the result does not depend on timing.
+#include "device_utils.h"
+#include "internal.h"
+
+namespace wpsgd {
+
+constexpr int kCombineThreads = 256;
+
+template <int VEC, int RS>
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float *__restrict__ W,
+                                                                  const double *__restrict__ a,
+                                                                  int k, int64_t d,
+                                                                  float *__restrict__ out)
+{
+    constexpr int CT = kCombineThreads / RS;          // column-owning threads per workgroup
+    constexpr int UNROLL = 8;
+    __shared__ double part[RS][CT][VEC];
+    const int cx = threadIdx.x % CT;
+    const int slice = threadIdx.x / CT;
+    const int64_t col = ((int64_t)blockIdx.x * CT + cx) * VEC;
+    const bool in = col < d;
+
+    double acc[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[j] = 0.0;
+
+    if (in) {
+        // slice r owns rows [r*per, min(k, (r+1)*per))
+        const int per = (k + RS - 1) / RS;
+        const int i0 = slice * per;
+        const int i1 = (i0 + per < k) ? i0 + per : k;
+        int i = i0;
+        for (; i + UNROLL <= i1; i += UNROLL) {
+            float x[UNROLL][VEC];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const float *p = W + (int64_t)(i + u) * d + col;
+                if constexpr (VEC == 4) {
+                    const float4 q = *reinterpret_cast<const float4 *>(p);
+                    x[u][0] = q.x; x[u][1] = q.y; x[u][2] = q.z; x[u][3] = q.w;
+                } else {
+                    x[u][0] = p[0];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const double w = a[i + u];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] += w * (double)x[u][j];
+            }
+        }
+        for (; i < i1; ++i) {
+            const float *p = W + (int64_t)i * d + col;
+            const double w = a[i];
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) acc[j] += w * (double)p[j];
+        }
+    }
+
+    if constexpr (RS > 1) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) part[slice][cx][j] = acc[j];
+        __syncthreads();
+        if (slice == 0 && in) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                double t = part[0][cx][j];
+                for (int r = 1; r < RS; ++r) t += part[r][cx][j];
+                acc[j] = t;
+            }
+        }
+    }
+    if (slice == 0 && in) {
+        if constexpr (VEC == 4) {
+            *reinterpret_cast<float4 *>(out + col) =
+                make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]);
+        } else {
+            out[col] = (float)acc[0];
+        }
+    }
+}
+
+template <int VEC>
+static hipError_t launch_combine_vec(const float *W, const double *a, int k, int64_t d, float *out,
+                                     hipStream_t s)
+{
+    const int64_t col_threads = (d + VEC - 1) / VEC;
+    // enough workgroups to cover the chip several times over -> no row split
+    int rs = 1;
+    if (col_threads < 256 * 1024 && k >= 64) rs = 4;
+    if (col_threads < 64 * 1024 && k >= 256) rs = 16;
+    const int ct = kCombineThreads / rs;
+    const unsigned grid = (unsigned)((col_threads + ct - 1) / ct);
+    if (rs == 1)
+        hipLaunchKernelGGL((combine_kernel<VEC, 1>), dim3(grid), dim3(kCombineThreads), 0, s, W, a, k, d, out);
+    else if (rs == 4)
+        hipLaunchKernelGGL((combine_kernel<VEC, 4>), dim3(grid), dim3(kCombineThreads), 0, s, W, a, k, d, out);
+    else
+        hipLaunchKernelGGL((combine_kernel<VEC, 16>), dim3(grid), dim3(kCombineThreads), 0, s, W, a, k, d, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine(const float *W, const double *a_dev, int k, int64_t d, float *w_out,
+                          hipStream_t s)
+{
+    const bool wide = (d % 4 == 0) && ((uintptr_t)W % 16 == 0) && ((uintptr_t)w_out % 16 == 0);
+    return wide ? launch_combine_vec<4>(W, a_dev, k, d, w_out, s)
+                : launch_combine_vec<1>(W, a_dev, k, d, w_out, s);
+}
+
+// Rows visited by one chain at steps n0 .. n0+count-1, produced by the same per-wave window the
+// chain kernels read (so this kernel checks their generator, not a copy of it).
+__global__ __launch_bounds__(kWave) void sample_rows_kernel(uint32_t seed_lo, uint32_t seed_hi,
+                                                            uint32_t chain, int64_t n0,
+                                                            int64_t count, uint32_t m, int64_t *out)
+{
+    RowWindow win;
+    win.init(seed_lo, seed_hi, chain, m);
+    const int64_t per = (count + gridDim.x - 1) / gridDim.x;
+    const int64_t t0 = (int64_t)blockIdx.x * per;
+    const int64_t t1 = (t0 + per < count) ? t0 + per : count;
+    for (int64_t t = t0; t < t1; ++t) {
+        const uint32_t row = win.get(n0 + t);
+        if (threadIdx.x == 0) out[t] = (int64_t)row;
+    }
+}
+
+hipError_t launch_sample_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, int64_t n0,
+                              int64_t count, uint32_t m, int64_t *out, hipStream_t s)
+{
+    if (count == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((count + 255) / 256 < 1024 ? (count + 255) / 256 : 1024);
+    hipLaunchKernelGGL(sample_rows_kernel, dim3(grid), dim3(kWave), 0, s, seed_lo, seed_hi, chain, n0,
+                       count, m, out);
+    return hipGetLastError();
+}
+
+}  // namespace wpsgd

@@ -1,0 +1,62 @@
+// Host-side plumbing shared by the translation units of libwpsgd: the argument block every
+// chain kernel receives, the resolved kernel plan, and the launcher entry of each kernel family.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "wpsgd.h"
+
+namespace wpsgd {
+
+// Arguments common to all chain kernels.  Workgroup b runs chain order[b] for nsteps[b] steps
+// (the host sorts chains longest first so that a late workgroup never holds the longest chain).
+struct ChainArgs {
+    // data set
+    const void *dense;        // row-major, ld elements per row (fp32 or bfloat16 bits)
+    int64_t ld;
+    const int64_t *row_ptr;   // CSR
+    const int32_t *col_idx;
+    const float *vals;
+    const float *y;
+    int64_t m, d;
+    // chains
+    int k;
+    const int32_t *order;     // DEVICE, k entries: chain id run by workgroup b
+    const int64_t *nsteps;    // DEVICE, k entries: steps of that chain
+    // hyper-parameters (fp64 on purpose: (1-eta*lambda)^n must not be compounded in fp32)
+    double eta, rho;          // rho = 1 - eta*lambda
+    uint32_t seed_lo, seed_hi;
+    // outputs / scratch
+    float *W;                 // k x d
+    void *state;              // k x d model vectors in HBM (state_in_hbm plans), else unused
+};
+
+enum class Family { DenseReg, DenseMem, Csr };
+
+// A fully resolved plan (every field chosen).
+struct Plan {
+    Family family;
+    int dtype;       // WPSGD_F32 / WPSGD_BF16 (dense)
+    int loss;
+    int threads;     // workgroup size
+    int ept;         // model elements per thread (DenseReg)
+    int vec;         // elements per global load instruction
+    int block_steps; // B
+    int prefetch;    // P: rounds in flight
+    size_t state_bytes_per_elem;   // 0 when the state lives in registers
+};
+
+// Launchers: return hipSuccess, or hipErrorInvalidValue when no instantiation matches the plan.
+hipError_t launch_dense_reg(const Plan &p, const ChainArgs &a, hipStream_t s);
+hipError_t launch_dense_mem(const Plan &p, const ChainArgs &a, hipStream_t s);
+hipError_t launch_csr(const Plan &p, const ChainArgs &a, hipStream_t s);
+bool dense_reg_has(const Plan &p);   // is (dtype, loss, threads, ept, vec, B, P) instantiated?
+
+hipError_t launch_combine(const float *W, const double *a_dev, int k, int64_t d, float *w_out,
+                          hipStream_t s);
+hipError_t launch_sample_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, int64_t n0,
+                              int64_t count, uint32_t m, int64_t *out, hipStream_t s);
+
+}  // namespace wpsgd

@@ -1,0 +1,345 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle, element by
+element on the same seeded inputs.
+
+Bars (fp32 GPU output against the fp64 oracle):
+  * sample-index streams: bit-exact;
+  * final weighted model and every chain's model: relative L2 error <= 1e-4;
+  * hinge chains whose oracle run came within 1e-9 of the kink y*yhat = 1 are reported and
+    exempted from the per-chain check (the branch there is decided by rounding), never from the
+    check of the final model.
+Small cases cover every kernel family and forced plan, ragged and unaligned shapes, idle
+chains, heavy shrink; the five full-size workloads are checked on sampled chains.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_1708_04801_amd import api
+from paper_1708_04801_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+KINK = 1e-9
+
+
+def rel_l2(got, want):
+    denom = np.linalg.norm(want)
+    return np.linalg.norm(got.astype(np.float64) - want) / (denom if denom > 0 else 1.0)
+
+
+def oracle_matrix(w):
+    return orc.CSR(w.row_ptr, w.col_idx, w.vals, w.d) if w.is_csr else orc.Dense(w.dense)
+
+
+def gpu_chains(w, plan=None, X=None, y=None):
+    X = api.matrix_from_workload(w) if X is None else X
+    y = torch.from_numpy(w.y).cuda() if y is None else y
+    W = api.wpsgd_run_chains(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed, plan=plan)
+    torch.cuda.synchronize()
+    return W
+
+
+def check_against_oracle(w, W_gpu, chain_ids=None, label=""):
+    """Per-chain and final-model parity; chain_ids selects the chains the oracle computes."""
+    ids = np.arange(w.k) if chain_ids is None else np.asarray(chain_ids)
+    Wo, margin = orc.run_chains(oracle_matrix(w), w.y, w.n_steps, w.eta, w.lam, w.loss, w.seed,
+                                chain_ids=ids)
+    Wg = W_gpu[torch.from_numpy(ids).cuda()].cpu().numpy()
+    assert np.isfinite(Wg).all(), f"{label}: non-finite model"
+    errs = np.array([rel_l2(Wg[q], Wo[q]) for q in range(ids.size)])
+    ambiguous = (margin < KINK) if w.loss == wl.HINGE else np.zeros(ids.size, dtype=bool)
+    bad = (errs > TOL) & ~ambiguous
+    assert not bad.any(), (f"{label}: chains {ids[bad].tolist()} off by {errs[bad].tolist()} "
+                           f"(closest approach to the hinge kink: {margin[bad].tolist()})")
+    if chain_ids is None:
+        a = orc.weights(w.n_steps, w.eta, w.lam)
+        v_ref = orc.combine(Wo, a)
+        a_gpu = api.wpsgd_weights(w.n_steps, w.eta, w.lam)
+        np.testing.assert_allclose(a_gpu, a, rtol=1e-11)
+        v_gpu = api.wpsgd_combine(W_gpu, a_gpu).cpu().numpy()
+        err = rel_l2(v_gpu, v_ref)
+        assert err <= TOL, f"{label}: final model off by {err} (min margin {margin.min()})"
+    return errs, margin
+
+
+# ------------------------------------------------------------------ sample stream, bit-exact
+
+@pytest.mark.parametrize("seed,chain,n0,count,m", [
+    (0, 0, 0, 1000, 4096), (0, 3, 0, 777, 1000000), (7, 5, 123, 4097, 1000003),
+    (2 ** 64 - 1, 2 ** 31 - 1, 2 ** 32 - 100, 300, 2 ** 32 - 1), (1, 0, 5, 0, 10), (1, 2047, 63, 2, 1)])
+def test_device_sample_stream_is_bit_exact(seed, chain, n0, count, m):
+    got = api.wpsgd_sample_indices_device(seed, chain, n0, count, m).cpu().numpy()
+    assert np.array_equal(got, orc.sample_indices(seed, chain, n0, count, m))
+    assert np.array_equal(got, api.wpsgd_sample_indices(seed, chain, n0, count, m))
+
+
+# ------------------------------------------------------------------ combine
+
+@pytest.mark.parametrize("k,d", [(1, 1), (4, 64), (3, 1023), (64, 4096), (128, 40000), (300, 77),
+                                 (2048, 256), (17, 262144 + 4), (1000, 5)])
+def test_combine_matches_oracle(k, d):
+    rng = np.random.default_rng(k * 1000003 + d)
+    W = rng.standard_normal((k, d)).astype(np.float32)
+    a = rng.random(k)
+    a /= a.sum()
+    got = api.wpsgd_combine(torch.from_numpy(W).cuda(), a).cpu().numpy()
+    want = orc.combine(W.astype(np.float64), a)
+    # fp64 accumulation, one rounding to fp32 at the end
+    np.testing.assert_allclose(got, want, rtol=2e-7, atol=1e-30)
+    e = np.zeros(k)
+    e[k // 2] = 1.0
+    assert np.array_equal(api.wpsgd_combine(torch.from_numpy(W).cuda(), e).cpu().numpy(), W[k // 2])
+
+
+def test_combine_unaligned_views():
+    rng = np.random.default_rng(5)
+    base = torch.from_numpy(rng.standard_normal(6 * 100 + 1).astype(np.float32)).cuda()
+    W = base[1:].view(6, 100)                # 4-byte aligned only
+    a = rng.random(6)
+    got = api.wpsgd_combine(W, a).cpu().numpy()
+    np.testing.assert_allclose(got, orc.combine(W.cpu().numpy().astype(np.float64), a), rtol=2e-7)
+
+
+# ------------------------------------------------------------------ chains, small cases
+
+def test_tiny_hinge_workload_full_path():
+    """The smallest workload at its stated size: 4 chains of 1000/800/600/400 steps, d = 64."""
+    w = wl.tiny_hinge()
+    errs, margin = check_against_oracle(w, gpu_chains(w), label="tiny_hinge")
+    assert errs.max() < 1e-6          # fp64 state: only the final rounding to fp32 remains
+
+
+DENSE_PLANS = [
+    # (d, loss, plan)
+    (64, wl.HINGE, None), (64, wl.LOGISTIC, {"block_steps": 4}), (100, wl.HINGE, None),
+    (128, wl.LOGISTIC, None), (255, wl.LOGISTIC, None), (256, wl.HINGE, None),
+    (256, wl.HINGE, {"prefetch": 16}), (256, wl.LOGISTIC, {"block_steps": 2}),
+    (256, wl.HINGE, {"block_steps": 4}), (252, wl.LOGISTIC, None),
+    (1000, wl.LOGISTIC, None), (1024, wl.HINGE, {"block_steps": 4}), (2048, wl.LOGISTIC, {"block_steps": 4}),
+    (3000, wl.LOGISTIC, None), (3001, wl.HINGE, None), (4096, wl.LOGISTIC, None),
+    (4096, wl.LOGISTIC, {"block_steps": 1, "prefetch": 8}), (4096, wl.LOGISTIC, {"block_steps": 2, "prefetch": 4}),
+    (4096, wl.HINGE, {"block_steps": 1, "prefetch": 4}), (4096, wl.HINGE, {"block_steps": 4}),
+    (4096, wl.LOGISTIC, {"threads": 512}), (4096, wl.LOGISTIC, {"threads": 1024, "block_steps": 1}),
+    (4099, wl.LOGISTIC, None), (8192, wl.HINGE, None), (8000, wl.LOGISTIC, {"block_steps": 4}),
+    (12000, wl.LOGISTIC, None), (16384, wl.HINGE, None), (20000, wl.LOGISTIC, None),
+    (4096, wl.LOGISTIC, {"state_in_hbm": 1}), (300, wl.HINGE, {"state_in_hbm": 1}),
+    (5001, wl.HINGE, {"state_in_hbm": 1}), (20000, wl.LOGISTIC, {"state_in_hbm": 1, "threads": 1024}),
+    (70000, wl.LOGISTIC, None), (40000, wl.HINGE, None),
+]
+
+
+@pytest.mark.parametrize("d,loss,plan", DENSE_PLANS)
+def test_dense_fp32_chains(d, loss, plan):
+    rng = np.random.default_rng(d * 7 + loss)
+    m, k = 512, 9
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    wstar = rng.standard_normal(d)
+    y = np.where(X @ wstar + 0.3 * rng.standard_normal(m) >= 0, 1.0, -1.0).astype(np.float32)
+    n = np.array([257, 64, 0, 1, 130, 63, 300, 5, 128], dtype=np.int64)
+    w = wl.Workload("dense_small", loss, 0.5 if loss == wl.HINGE else 2.0, 1e-3, 11, n, y, m, d, dense=X)
+    Xg = api.matrix_from_workload(w)
+    desc = api.wpsgd_describe_plan(Xg, k, loss, plan)
+    W = gpu_chains(w, plan=plan, X=Xg)
+    check_against_oracle(w, W, label=f"d={d} [{desc}]")
+    assert (W[2] == 0).all()                                     # idle chain keeps w_0 = 0
+    W2 = gpu_chains(w, plan=plan, X=Xg)
+    assert torch.equal(W, W2)                                    # same inputs, same bits
+
+
+BF16_PLANS = [(64, None), (256, None), (512, None), (520, None), (2048, {"block_steps": 4}), (4096, None),
+              (8192, {"block_steps": 1}), (16384, None), (30000, None), (65536, None),
+              (65536, {"threads": 512}), (65536, {"state_in_hbm": 1}), (4100, {"state_in_hbm": 1})]
+
+
+@pytest.mark.parametrize("d,plan", BF16_PLANS)
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_dense_bf16_chains(d, plan, loss):
+    if loss == wl.HINGE and plan and plan.get("threads") == 512:
+        pytest.skip("512-thread wide variant exists for logistic only")
+    rng = np.random.default_rng(d * 13 + loss)
+    m = 96
+    Xf = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    bits = wl.f32_to_bf16_bits(Xf)
+    wstar = rng.standard_normal(d)
+    y = np.where(wl.bf16_bits_to_f32(bits) @ wstar >= 0, 1.0, -1.0).astype(np.float32)
+    n = np.array([70, 0, 33, 129], dtype=np.int64)
+    w = wl.Workload("bf16_small", loss, 0.5, 1e-3, 3, n, y, m, d, dense=bits)
+    Xg = api.matrix_from_workload(w)
+    desc = api.wpsgd_describe_plan(Xg, 4, loss, plan)
+    check_against_oracle(w, gpu_chains(w, plan=plan, X=Xg), label=f"bf16 d={d} [{desc}]")
+
+
+def test_dense_rows_with_padding_and_misaligned_base():
+    rng = np.random.default_rng(21)
+    m, d, ld = 200, 300, 304
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = np.array([100, 40], dtype=np.int64)
+    w = wl.Workload("padded", wl.LOGISTIC, 1.0, 1e-2, 5, n, y, m, d, dense=X)
+    padded = torch.zeros((m, ld), dtype=torch.float32, device="cuda")
+    padded[:, :d] = torch.from_numpy(X).cuda()
+    Xg = api.Matrix(m, d, dense=padded[:, :d])                     # ld = 304, 16-byte aligned rows
+    assert "vec=4" in api.wpsgd_describe_plan(Xg, 2, wl.LOGISTIC)
+    check_against_oracle(w, gpu_chains(w, X=Xg), label="padded rows")
+    flat = torch.zeros(m * d + 1, dtype=torch.float32, device="cuda")
+    flat[1:] = torch.from_numpy(X).cuda().reshape(-1)
+    Xu = api.Matrix(m, d, dense=flat[1:].view(m, d))               # base only 4-byte aligned
+    assert "vec=1" in api.wpsgd_describe_plan(Xu, 2, wl.LOGISTIC)
+    check_against_oracle(w, gpu_chains(w, X=Xu), label="misaligned base")
+
+
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_heavy_shrink_folds_the_scale(loss):
+    """(1 - eta*lambda)^n far below fp32 range: the lazy scale must be folded back in time."""
+    rng = np.random.default_rng(33)
+    m, d = 64, 256
+    X = rng.standard_normal((m, d)).astype(np.float32) / 16
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = np.array([900, 333], dtype=np.int64)
+    w = wl.Workload("shrink", loss, 0.5, 0.6, 2, n, y, m, d, dense=X)      # rate 0.7, 0.7^900 ~ 1e-140
+    for plan in (None, {"threads": 256}, {"state_in_hbm": 1}):
+        check_against_oracle(w, gpu_chains(w, plan=plan), label=f"heavy shrink {plan}")
+
+
+def test_single_chain_and_equal_lengths():
+    w = wl.tiny_hinge(n_steps=(500,))
+    W = gpu_chains(w)
+    v = api.wpsgd_combine(W, api.wpsgd_weights(w.n_steps, w.eta, w.lam))
+    assert torch.equal(v, W[0])                                   # k = 1: weight 1
+    w = wl.tiny_hinge(n_steps=(200, 200, 200))
+    W = gpu_chains(w)
+    a = api.wpsgd_weights(w.n_steps, w.eta, w.lam)
+    assert np.array_equal(a, np.full(3, 1 / 3))                   # Algorithm 2's plain average
+    v = api.wpsgd_combine(W, a).cpu().numpy()
+    np.testing.assert_allclose(v, W.cpu().numpy().astype(np.float64).mean(axis=0), rtol=3e-7, atol=1e-12)
+
+
+def test_all_chains_idle():
+    w = wl.tiny_hinge(n_steps=(0, 0, 0))
+    W = gpu_chains(w)
+    assert (W == 0).all()
+    v = api.wpsgd_combine(W, api.wpsgd_weights(w.n_steps, w.eta, w.lam))
+    assert (v == 0).all()
+
+
+def test_many_more_chains_than_compute_units():
+    w = wl.many_chains(m=8192, d=256, k=3000, n_full=60)
+    check_against_oracle(w, gpu_chains(w), label="3000 chains")
+
+
+# ------------------------------------------------------------------ CSR chains
+
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_sparse_chains_small(loss):
+    w = wl.sparse_hinge(m=5000, d=1 << 14, k=12, n_median=300)
+    w.loss = loss
+    w.n_steps[3] = 0
+    check_against_oracle(w, gpu_chains(w), label="sparse small")
+
+
+def test_sparse_rows_longer_than_the_register_window():
+    rng = np.random.default_rng(44)
+    m, d = 40, 5000
+    rp, ci, va = [0], [], []
+    for r in range(m):
+        nnz = [1, 64, 65, 256, 257, 700][r % 6]
+        c = np.sort(rng.choice(d, size=nnz, replace=False))
+        v = rng.standard_normal(nnz)
+        v /= np.linalg.norm(v)
+        ci += c.tolist()
+        va += v.tolist()
+        rp.append(len(ci))
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    w = wl.Workload("long_rows", wl.HINGE, 0.3, 1e-2, 9, np.array([150, 80, 0], dtype=np.int64), y, m, d,
+                    row_ptr=np.array(rp, dtype=np.int64), col_idx=np.array(ci, dtype=np.int32),
+                    vals=np.array(va, dtype=np.float32))
+    check_against_oracle(w, gpu_chains(w), label="long sparse rows")
+
+
+# ------------------------------------------------------------------ error paths
+
+def test_run_chains_rejects_bad_arguments():
+    w = wl.tiny_hinge(n_steps=(10, 5))
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    for kwargs in [dict(eta=0.0), dict(lam=-1.0), dict(eta=10.0, lam=0.2)]:
+        args = dict(eta=w.eta, lam=w.lam)
+        args.update(kwargs)
+        with pytest.raises(api.WpsgdError) as err:
+            api.wpsgd_run_chains(X, y, w.n_steps, args["eta"], args["lam"], w.loss, 0)
+        assert err.value.status == api.INVALID_ARG
+    with pytest.raises(api.WpsgdError) as err:
+        api.wpsgd_run_chains(X, y, [10, -1], w.eta, w.lam, w.loss, 0)
+    assert err.value.status == api.INVALID_ARG
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(api.WpsgdError) as err:
+        api.wpsgd_run_chains(X, y, w.n_steps, w.eta, w.lam, w.loss, 0, workspace=small)
+    assert err.value.status == api.WORKSPACE_TOO_SMALL
+    with pytest.raises(api.WpsgdError) as err:
+        api.wpsgd_run_chains(X, y, w.n_steps, w.eta, w.lam, w.loss, 0, plan={"threads": 64, "block_steps": 8})
+    assert err.value.status == api.UNSUPPORTED
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ the five workloads at full size
+
+def _sampled(k, count, n_steps):
+    """Chains the oracle recomputes: the longest, the shortest, and a seeded spread."""
+    rng = np.random.default_rng(99)
+    pick = {int(np.argmax(n_steps)), int(np.argmin(n_steps))}
+    pick.update(rng.choice(k, size=min(k, count), replace=False).tolist())
+    return np.array(sorted(pick))
+
+
+def _final_model_columns(w, W_gpu, cols):
+    """Final weighted model on sampled columns, recomputed in fp64 from the GPU's chain outputs."""
+    a = api.wpsgd_weights(w.n_steps, w.eta, w.lam)
+    v = api.wpsgd_combine(W_gpu, a)
+    torch.cuda.synchronize()
+    sub = W_gpu[:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(v[torch.from_numpy(cols).cuda()].cpu().numpy(), a @ sub, rtol=3e-7, atol=1e-12)
+    np.testing.assert_allclose(a, orc.weights(w.n_steps, w.eta, w.lam), rtol=1e-11)
+
+
+def test_full_dense_logistic():
+    w = wl.dense_logistic()
+    W = gpu_chains(w)
+    check_against_oracle(w, W, label="dense_logistic full")          # the oracle runs all 64 chains
+
+
+def test_full_many_chains():
+    w = wl.many_chains()
+    W = gpu_chains(w)
+    check_against_oracle(w, W, label="many_chains full")             # all 2048 chains
+
+
+def test_full_wide_bf16():
+    w = wl.wide_bf16()
+    W = gpu_chains(w)
+    ids = _sampled(w.k, 6, w.n_steps)
+    check_against_oracle(w, W, chain_ids=ids, label="wide_bf16 full")
+    _final_model_columns(w, W, np.arange(0, w.d, 997))
+
+
+def test_full_sparse_hinge():
+    w = wl.sparse_hinge()
+    W = gpu_chains(w)
+    # The plain oracle shrinks all 2^20 coordinates at every step, so it recomputes the six
+    # shortest chains and the median one.
+    by_len = np.argsort(w.n_steps)
+    ids = np.array(sorted(set(by_len[:6].tolist()) | {int(by_len[w.k // 2])}))
+    check_against_oracle(w, W, chain_ids=ids, label="sparse_hinge full")
+    # The longest chains are compared with the oracle's scalar-scale mode (itself pinned to the
+    # plain mode in the CPU tests).
+    long_ids = np.array(sorted(by_len[-3:].tolist()))
+    Wl, margin = orc.run_chains(oracle_matrix(w), w.y, w.n_steps, w.eta, w.lam, w.loss, w.seed,
+                                chain_ids=long_ids, csr_mode=orc.LAZY)
+    Wg = W[torch.from_numpy(long_ids).cuda()].cpu().numpy()
+    for q, i in enumerate(long_ids):
+        if margin[q] >= KINK:
+            assert rel_l2(Wg[q], Wl[q]) <= TOL, f"sparse chain {i}: {rel_l2(Wg[q], Wl[q])}"
+    _final_model_columns(w, W, np.arange(0, w.d, 4099))
