@@ -30,7 +30,11 @@ constexpr int kLoss = WPSGD_LOSS;
 // The EPT elements of one row that a thread owns.  Element e of the fragment is column
 //   ((e / VEC) * NT + tid) * VEC + e % VEC
 // so that every load instruction of a wave covers one contiguous 64*VEC-element span.
-template <typename TX, int NT, int EPT, int VEC>
+// Loads are unconditional (a lane past the end of the row re-reads the row's first elements and
+// discards them): a load that may or may not be issued would force the wait before each use to
+// drain every outstanding load, and the prefetch with it.  FULL says NT*EPT == d, i.e. no lane
+// is ever past the end and the discard is compiled out.
+template <typename TX, int NT, int EPT, int VEC, bool FULL>
 struct RowFrag {
     static constexpr bool kPacked = (sizeof(TX) == 2) && (VEC == 8);
     static constexpr int kWords = kPacked ? EPT / 2 : EPT;
@@ -42,22 +46,23 @@ struct RowFrag {
 #pragma unroll
         for (int c = 0; c < EPT / VEC; ++c) {
             const int64_t col = ((int64_t)c * NT + tid) * VEC;
-            const bool in = col < d;            // d is a multiple of VEC whenever VEC > 1
+            const bool in = FULL || col < d;        // d is a multiple of VEC whenever VEC > 1
+            const TX *p = row + (in ? col : 0);
             if constexpr (VEC == 1) {
+                uint32_t q;
                 if constexpr (sizeof(TX) == 2) {
-                    w[c] = in ? ((uint32_t)row[col] << 16) : 0u;
+                    q = (uint32_t)p[0] << 16;
                 } else {
-                    w[c] = in ? __float_as_uint(row[col]) : 0u;
+                    q = __float_as_uint(p[0]);
                 }
-            } else if constexpr (kPacked) {
-                uint4 q = make_uint4(0u, 0u, 0u, 0u);
-                if (in) q = *reinterpret_cast<const uint4 *>(row + col);
-                w[4 * c + 0] = q.x; w[4 * c + 1] = q.y; w[4 * c + 2] = q.z; w[4 * c + 3] = q.w;
+                w[c] = in ? q : 0u;
             } else {
-                static_assert(sizeof(TX) == 4 && VEC == 4, "fp32 rows load as 4-vectors");
-                uint4 q = make_uint4(0u, 0u, 0u, 0u);
-                if (in) q = *reinterpret_cast<const uint4 *>(row + col);
-                w[4 * c + 0] = q.x; w[4 * c + 1] = q.y; w[4 * c + 2] = q.z; w[4 * c + 3] = q.w;
+                static_assert(kPacked || (sizeof(TX) == 4 && VEC == 4), "16-byte loads only");
+                const uint4 q = *reinterpret_cast<const uint4 *>(p);
+                w[4 * c + 0] = in ? q.x : 0u;
+                w[4 * c + 1] = in ? q.y : 0u;
+                w[4 * c + 2] = in ? q.z : 0u;
+                w[4 * c + 3] = in ? q.w : 0u;
             }
         }
     }
@@ -73,14 +78,15 @@ struct RowFrag {
 
 // TX and LOSS are template parameters (not just per-file constants) so that the four builds of
 // this file produce four distinct sets of kernel symbols.
-template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P>
+template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P, bool FULL>
 __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 {
-    using TV = typename StateType<LOSS>::type;
+    using TV = typename StateType<LOSS>::type;     // state, dot products and the step recursion
     constexpr int NW = NT / kWave;
     constexpr int NG = B * (B - 1) / 2;
     constexpr int NR = B + NG;
-    __shared__ TV red[2][NW][NR];
+    constexpr int NACC = EPT >= 4 ? 4 : EPT;       // independent partial sums per dot product
+    __shared__ TV red[2][NR][NW];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -92,10 +98,11 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     TV v[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) v[e] = (TV)0;
-    double s = 1.0, inv_s = 1.0;
-    const double rho = a.rho, inv_rho = 1.0 / a.rho, eta = a.eta;
+    // w = s*v.  s and eta/s are fp64 and advance independently of the data.
+    double s = 1.0, eta_over_s = a.eta;
+    const double rho = a.rho, inv_rho = 1.0 / a.rho;
 
-    RowFrag<TX, NT, EPT, VEC> x[P][B];
+    RowFrag<TX, NT, EPT, VEC, FULL> x[P][B];
     float yv[P][B];
     RowWindow win;
     win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
@@ -109,78 +116,98 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             step = step < n ? step : n - 1;
             const uint32_t row = win.get(step);
             x[u][b].load(X + (int64_t)row * a.ld, a.d, tid);
-            yv[u][b] = a.y[row];
+            // The label travels with the row through the vector-memory queue.  As a scalar
+            // load it would be re-issued right before its use (scalar registers are scarce
+            // here) and put a cache miss on the dependent path of every step.
+            uint32_t row_v = row;
+            asm volatile("" : "+v"(row_v));
+            yv[u][b] = a.y[row_v];
         }
     };
 
     int parity = 0;
     auto consume = [&](int u, int64_t blk) {
-        TV acc[NR];
+        // p_b = v.x_b and G_qb = x_q.x_b, each as NACC interleaved partial sums
+        TV acc[NR][NACC];
 #pragma unroll
-        for (int r = 0; r < NR; ++r) acc[r] = (TV)0;
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int j = 0; j < NACC; ++j) acc[r][j] = (TV)0;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
             TV xe[B];
 #pragma unroll
             for (int b = 0; b < B; ++b) xe[b] = (TV)x[u][b].at(e);
 #pragma unroll
-            for (int b = 0; b < B; ++b) acc[b] += v[e] * xe[b];
+            for (int b = 0; b < B; ++b) acc[b][e % NACC] += v[e] * xe[b];
             int g = B;
 #pragma unroll
             for (int q = 0; q < B; ++q)
 #pragma unroll
-                for (int b = q + 1; b < B; ++b) acc[g++] += xe[q] * xe[b];
+                for (int b = q + 1; b < B; ++b) acc[g++][e % NACC] += xe[q] * xe[b];
         }
+        TV tot[NR];
 #pragma unroll
-        for (int r = 0; r < NR; ++r) acc[r] = wave_sum(acc[r]);
+        for (int r = 0; r < NR; ++r) {
+            TV t = acc[r][0];
+#pragma unroll
+            for (int j = 1; j < NACC; ++j) t += acc[r][j];
+            tot[r] = wave_sum_lane63(t);
+        }
         if constexpr (NW > 1) {
-            if (lane == 0) {
+            if (lane == kWave - 1) {
 #pragma unroll
-                for (int r = 0; r < NR; ++r) red[parity][wave][r] = acc[r];
+                for (int r = 0; r < NR; ++r) red[parity][r][wave] = tot[r];
             }
             __syncthreads();
 #pragma unroll
             for (int r = 0; r < NR; ++r) {
-                TV t = red[parity][0][r];
+                TV t = red[parity][r][0];
 #pragma unroll
-                for (int w = 1; w < NW; ++w) t += red[parity][w][r];
-                acc[r] = t;
+                for (int w = 1; w < NW; ++w) t += red[parity][r][w];
+                tot[r] = t;
             }
             parity ^= 1;
+        } else {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
         }
         // the B dependent steps, as scalars
-        double c[B];
+        TV c[B];
 #pragma unroll
         for (int b = 0; b < B; ++b) {
-            double dot = (double)acc[b];
+            TV dot = tot[b];
             int g = B;
 #pragma unroll
             for (int q = 0; q < B; ++q)
 #pragma unroll
                 for (int bb = q + 1; bb < B; ++bb) {
-                    if (bb == b) dot += c[q] * (double)acc[g];
+                    if (bb == b) dot += c[q] * tot[g];
                     ++g;
                 }
             const bool live = blk * B + b < n;
-            const double slope = loss_slope<LOSS>((double)yv[u][b], s * dot);
-            if (live) {
-                s *= rho;
-                inv_s *= inv_rho;
-                c[b] = -eta * slope * inv_s;
+            const double s_next = live ? s * rho : s;
+            const double eos_next = live ? eta_over_s * inv_rho : 0.0;     // eta / s_next
+            if constexpr (LOSS == kLossHinge) {
+                c[b] = step_coef_hinge((double)yv[u][b], dot, s, eos_next);
             } else {
-                c[b] = 0.0;
+                c[b] = step_coef_logistic(yv[u][b], dot, (float)s, (float)eos_next);
+            }
+            if (live) {
+                s = s_next;
+                eta_over_s = eos_next;
             }
         }
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
 #pragma unroll
-            for (int b = 0; b < B; ++b) v[e] += (TV)c[b] * (TV)x[u][b].at(e);
+            for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
         }
-        if (s < 0x1p-30) {          // fold the scale into v long before 1/s leaves fp32 range
+        if (s < 0x1p-30) {          // fold the scale into v long before eta/s leaves fp32 range
 #pragma unroll
             for (int e = 0; e < EPT; ++e) v[e] *= (TV)s;
             s = 1.0;
-            inv_s = 1.0;
+            eta_over_s = a.eta;
         }
     };
 
@@ -206,7 +233,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
-        if (col < a.d) out[col] = (float)(s * (double)v[e]);
+        if (FULL || col < a.d) out[col] = (float)(s * (double)v[e]);
     }
 }
 
@@ -265,8 +292,12 @@ hipError_t WPSGD_CAT(dense_reg_dispatch_, WPSGD_SUFFIX)(Plan &p, const ChainArgs
         p.block_steps = BB;                                                                    \
         p.prefetch = PP;                                                                       \
         if (a) {                                                                               \
-            hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP>), dim3(a->k), dim3(NT), \
-                               0, s, *a);                                                      \
+            if ((int64_t)NT * EPT == a->d)                                                     \
+                hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP, true>),  \
+                                   dim3(a->k), dim3(NT), 0, s, *a);                            \
+            else                                                                               \
+                hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP, false>), \
+                                   dim3(a->k), dim3(NT), 0, s, *a);                            \
             return hipGetLastError();                                                          \
         }                                                                                      \
         return hipSuccess;                                                                     \

@@ -75,20 +75,63 @@ struct RowWindow {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Wavefront sum, result in every lane.  Butterfly over lane ^ 1, 2, 4, 8, 16, 32.
+// Wavefront sums on the DPP cross-lane network (no LDS traffic).
+//
+// dpp_move<CTRL, ROW_MASK>(x): every lane of an enabled 16-lane row receives x from the lane
+// CTRL names; lanes of disabled rows receive 0.  Controls used (GFX9 encodings):
+//   0xB1 quad_perm[1,0,3,2] (lane^1)   0x4E quad_perm[2,3,0,1] (lane^2)
+//   0x141 row_half_mirror (7 - lane%8) 0x140 row_mirror (15 - lane%16)
+//   0x142 row_bcast15: lane 15 of each row to every lane of the next row
+//   0x143 row_bcast31: lane 31 to every lane of rows 2 and 3
+// After the four in-row steps all 16 lanes of a row hold the row sum; bcast15 into rows 1 and 3,
+// then bcast31 into rows 2 and 3, leaves the wave total in row 3, i.e. in lane 63.
 // ---------------------------------------------------------------------------------------------
-__device__ inline float wave_sum(float v)
+template <int CTRL, int ROW_MASK>
+__device__ inline float dpp_move(float x)
 {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, false));
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ inline double dpp_move(double x)
+{
+    const long long bits = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(bits & 0xFFFFFFFFLL), CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+
+// Sum over the 64 lanes; the result is valid in lane 63 only.
+template <typename T>
+__device__ inline T wave_sum_lane63(T v)
+{
+    v += dpp_move<0xB1, 0xF>(v);
+    v += dpp_move<0x4E, 0xF>(v);
+    v += dpp_move<0x141, 0xF>(v);
+    v += dpp_move<0x140, 0xF>(v);
+    v += dpp_move<0x142, 0xA>(v);
+    v += dpp_move<0x143, 0xC>(v);
     return v;
 }
 
-__device__ inline double wave_sum(double v)
+__device__ inline float read_lane63(float v)
 {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), kWave - 1));
+}
+
+__device__ inline double read_lane63(double v)
+{
+    const long long bits = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)(bits & 0xFFFFFFFFLL), kWave - 1);
+    const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), kWave - 1);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+
+// Sum over the 64 lanes, result in every lane.
+template <typename T>
+__device__ inline T wave_sum(T v)
+{
+    return read_lane63(wave_sum_lane63(v));
 }
 
 // bfloat16 is the upper half of a binary32: widening is a shift.
@@ -105,6 +148,23 @@ __device__ inline double loss_slope(double y, double yhat)
     } else {
         return -y / (1.0 + exp(y * yhat));
     }
+}
+
+// Coefficient of one step in the scaled representation w = s*v:  v <- v + c*x with
+//   c = -eta * dL/dyhat(y, s*dot) / s_next,   dot = v.x,   s_next = (1-eta*lambda)*s.
+// eta_over_s_next = eta / s_next is handed in so that it stays off the dependent path.
+// Hinge decides y*yhat < 1 in fp64.  Logistic is smooth in yhat, so it runs on the fp32
+// hardware exponential and reciprocal (about 1e-6 relative error in c).
+__device__ inline double step_coef_hinge(double y, double dot, double s, double eta_over_s_next)
+{
+    return (y * (s * dot) < 1.0) ? y * eta_over_s_next : 0.0;
+}
+
+__device__ inline float step_coef_logistic(float y, float dot, float s, float eta_over_s_next)
+{
+    const float z = y * (s * dot);
+    const float e = __expf(z);                        // inf for large z -> c = 0; 0 for z << 0
+    return (y * eta_over_s_next) * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 // Model-vector precision by loss: the hinge slope is discontinuous in yhat, so a rounding-size
