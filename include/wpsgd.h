@@ -114,7 +114,7 @@ size_t wpsgd_combine_workspace(int k, int64_t d);
 int wpsgd_combine(const float *W, const double *a, int k, int64_t d, float *w_out,
                   void *workspace, size_t workspace_bytes, void *stream);
 
-/* ---- sample stream (stands for "shuffle, then take the n-th example", Algorithm 1) ----
+/* ---- sample stream (stands for the per-node shuffle and n-th-example fetch of Algorithm 1) ----
  * Row visited by chain `chain` at step n (0-based):
  *   (r0,..) = Philox4x32-10(counter = (n mod 2^32, n div 2^32, chain, 0),
  *                           key = (seed mod 2^32, seed div 2^32));   j = floor(r0 * m / 2^32).

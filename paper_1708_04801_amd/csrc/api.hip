@@ -72,7 +72,8 @@ static int dense_vec(const wpsgd_matrix *X)
 
 // Chooses the kernel family and its parameters.  Dense rows go to the register kernel when
 // some instantiated shape holds d elements, else to the HBM-state kernel.
-static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan *force, Plan *out)
+static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan *force, Plan *out,
+                        double rho = 1.0)
 {
     Plan p{};
     p.loss = (int)loss;
@@ -96,7 +97,11 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
 
     const int wide = dense_vec(X);
     p.vec = wide;
-    if (!f.state_in_hbm) {
+    // The register kernel folds its lazy scale once per 64 steps, which needs
+    // (1-eta*lambda)^64 to stay far inside fp32 range; a harsher shrink takes the HBM kernel,
+    // which checks every step.
+    const bool mild_shrink = rho >= 0.55;
+    if (!f.state_in_hbm && mild_shrink) {
         static const int kThreads[] = {64, 256, 512, 1024};
         static const int kEpt[] = {1, 2, 4, 8, 16, 32, 64, 128};
         // smallest workgroup first, then the smallest fragment that covers d; fragments much
@@ -137,6 +142,11 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
 }
 
 static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+static size_t state_elem_bytes(wpsgd_loss loss)
+{
+    return loss == WPSGD_HINGE ? sizeof(double) : sizeof(float);
+}
 
 static size_t header_bytes(int k)
 {
@@ -196,7 +206,9 @@ size_t wpsgd_run_chains_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss,
     if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return 0;
     Plan p;
     if (resolve_plan(X, loss, plan, &p) != WPSGD_OK) return 0;
-    return header_bytes(k) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
+    // Always room for the model vectors in HBM: which kernel runs also depends on eta*lambda,
+    // which this query does not see.
+    return header_bytes(k) + align256((size_t)k * (size_t)X->d * state_elem_bytes(loss));
 }
 
 int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *plan,
@@ -229,7 +241,7 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
     if (!(eta > 0.0) || !(lambda >= 0.0) || !(eta * lambda < 1.0)) return WPSGD_INVALID_ARG;
     if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
     Plan p;
-    rc = resolve_plan(X, loss, plan, &p);
+    rc = resolve_plan(X, loss, plan, &p, 1.0 - eta * lambda);
     if (rc != WPSGD_OK) return rc;
     const size_t need = header_bytes(k) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
     if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;

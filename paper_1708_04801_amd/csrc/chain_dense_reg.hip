@@ -3,16 +3,26 @@
 // One workgroup runs one chain (Algorithm 1, the inner loop of node i): NT threads own EPT model
 // elements each, so the vector never leaves the register file between the first and the last
 // step.  The step  w <- (1-eta*lambda) w - eta*g*x  (Eq. 5 with Eq. 4) is carried as w = s*v:
-// the shrink only touches the fp64 scalar s, the gradient part touches v.
+// the shrink only touches a scalar, the gradient part touches v.
 //
 // Because the rows a chain visits depend on (seed, chain, step) only, never on w, rows are
-// requested P rounds before they are consumed and wait in registers.  A round folds B steps into
-// one workgroup-wide reduction: with the rows x_0..x_{B-1} of the round and the vector v at its
-// start, the threads reduce p_b = v.x_b and G_ab = x_a.x_b (a<b) together; the B dependent
+// requested P-1 rounds before they are consumed and wait in registers.  A round folds B steps
+// into one workgroup-wide reduction: with the rows x_0..x_{B-1} of the round and the vector v at
+// its start, the threads reduce p_b = v.x_b and G_ab = x_a.x_b (a<b) together; the B dependent
 // steps are then a scalar recursion
 //     v_b.x_b = p_b + sum_{a<b} c_a G_ab,   yhat_b = s_b * (v_b.x_b),   c_b = -eta*g_b / s_{b+1}
 // and the round ends with the rank-B update v += sum_b c_b x_b.  This is the same arithmetic as
 // B single steps up to summation order; B = 1 is the plain step.
+//
+// What does not depend on w is prepared once per window of 64 steps, one step per lane: the
+// visited rows (Philox) and the two per-step scalars of the recursion, s_l and eta/s_{l+1} with
+// s_l = s_window * (1-eta*lambda)^l in fp64.  Inside a window a step fetches them with a lane
+// read, so its dependent path holds no integer hashing and no fp64 scale arithmetic.  Steps
+// past the end of the chain have eta/s = 0 in their lane and therefore change nothing: the loop
+// always runs whole groups of P rounds and needs no tail code.
+//
+// Rows are fetched with raw buffer loads: the row's address sits in a scalar descriptor, each
+// lane adds a fixed 32-bit offset, and lanes past the end of the row read zeros.
 //
 // This file is compiled once per (row storage, loss) pair; WPSGD_TX_BF16 and WPSGD_LOSS select it.
 #include "device_utils.h"
@@ -27,43 +37,41 @@ using RowElem = float;
 #endif
 constexpr int kLoss = WPSGD_LOSS;
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor over [base, base+bytes): dword-typed, reads past the end return 0.
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
 // The EPT elements of one row that a thread owns.  Element e of the fragment is column
 //   ((e / VEC) * NT + tid) * VEC + e % VEC
 // so that every load instruction of a wave covers one contiguous 64*VEC-element span.
-// Loads are unconditional (a lane past the end of the row re-reads the row's first elements and
-// discards them): a load that may or may not be issued would force the wait before each use to
-// drain every outstanding load, and the prefetch with it.  FULL says NT*EPT == d, i.e. no lane
-// is ever past the end and the discard is compiled out.
-template <typename TX, int NT, int EPT, int VEC, bool FULL>
+template <typename TX, int NT, int EPT, int VEC>
 struct RowFrag {
     static constexpr bool kPacked = (sizeof(TX) == 2) && (VEC == 8);
     static constexpr int kWords = kPacked ? EPT / 2 : EPT;
+    static constexpr int kChunks = EPT / VEC;
+    static_assert(EPT % VEC == 0, "fragment must be whole loads");
     uint32_t w[kWords];     // fp32 bit patterns, or pairs of bfloat16 when packed
 
-    __device__ inline void load(const TX *row, int64_t d, int tid)
+    // chunk c of the row behind `row`; off = this lane's byte offset of the chunk in a row
+    __device__ inline void load_chunk(int c, __amdgpu_buffer_rsrc_t row, uint32_t off)
     {
-        static_assert(EPT % VEC == 0, "fragment must be whole loads");
-#pragma unroll
-        for (int c = 0; c < EPT / VEC; ++c) {
-            const int64_t col = ((int64_t)c * NT + tid) * VEC;
-            const bool in = FULL || col < d;        // d is a multiple of VEC whenever VEC > 1
-            const TX *p = row + (in ? col : 0);
-            if constexpr (VEC == 1) {
-                uint32_t q;
-                if constexpr (sizeof(TX) == 2) {
-                    q = (uint32_t)p[0] << 16;
-                } else {
-                    q = __float_as_uint(p[0]);
-                }
-                w[c] = in ? q : 0u;
+        if constexpr (VEC == 1) {
+            if constexpr (sizeof(TX) == 2) {
+                w[c] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(row, off, 0, 0) << 16;
             } else {
-                static_assert(kPacked || (sizeof(TX) == 4 && VEC == 4), "16-byte loads only");
-                const uint4 q = *reinterpret_cast<const uint4 *>(p);
-                w[4 * c + 0] = in ? q.x : 0u;
-                w[4 * c + 1] = in ? q.y : 0u;
-                w[4 * c + 2] = in ? q.z : 0u;
-                w[4 * c + 3] = in ? q.w : 0u;
+                w[c] = __builtin_amdgcn_raw_buffer_load_b32(row, off, 0, 0);
             }
+        } else {
+            static_assert(kPacked || (sizeof(TX) == 4 && VEC == 4), "16-byte loads only");
+            const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(row, off, 0, 0);
+            w[4 * c + 0] = q[0];
+            w[4 * c + 1] = q[1];
+            w[4 * c + 2] = q[2];
+            w[4 * c + 3] = q[3];
         }
     }
     __device__ inline float at(int e) const
@@ -76,16 +84,32 @@ struct RowFrag {
     }
 };
 
+// Wave-uniform read of lane j of a per-lane table.
+__device__ inline float lane_read(float t, int j)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), j));
+}
+__device__ inline double lane_read(double t, int j)
+{
+    const long long bits = __double_as_longlong(t);
+    const int lo = __builtin_amdgcn_readlane((int)(bits & 0xFFFFFFFFLL), j);
+    const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), j);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+
 // TX and LOSS are template parameters (not just per-file constants) so that the four builds of
 // this file produce four distinct sets of kernel symbols.
-template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P, bool FULL>
+template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P>
 __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 {
     using TV = typename StateType<LOSS>::type;     // state, dot products and the step recursion
+    using Frag = RowFrag<TX, NT, EPT, VEC>;
     constexpr int NW = NT / kWave;
     constexpr int NG = B * (B - 1) / 2;
     constexpr int NR = B + NG;
     constexpr int NACC = EPT >= 4 ? 4 : EPT;       // independent partial sums per dot product
+    constexpr int D = B * P;                       // steps per group of P rounds
+    static_assert(kWave % D == 0, "a 64-step window must hold whole groups");
     __shared__ TV red[2][NR][NW];
 
     const int tid = threadIdx.x;
@@ -93,147 +117,204 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     const int wave = tid / kWave;
     const int chain = a.order[blockIdx.x];
     const int64_t n = a.nsteps[blockIdx.x];
-    const TX *X = static_cast<const TX *>(a.dense);
+    const char *X = static_cast<const char *>(a.dense);
+    const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
+    const uint32_t row_bytes = (uint32_t)(a.d * (int64_t)sizeof(TX));
+    float *out = a.W + (int64_t)chain * a.d;
 
     TV v[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) v[e] = (TV)0;
-    // w = s*v.  s and eta/s are fp64 and advance independently of the data.
-    double s = 1.0, eta_over_s = a.eta;
-    const double rho = a.rho, inv_rho = 1.0 / a.rho;
-
-    RowFrag<TX, NT, EPT, VEC, FULL> x[P][B];
-    float yv[P][B];
-    RowWindow win;
-    win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
-
-    // Request the rows of round `blk` into slot u.  Steps past the end of the chain re-request
-    // the chain's last row (a cache hit) so that the loop body has no data-dependent branches.
-    auto request = [&](int u, int64_t blk) {
-#pragma unroll
-        for (int b = 0; b < B; ++b) {
-            int64_t step = blk * B + b;
-            step = step < n ? step : n - 1;
-            const uint32_t row = win.get(step);
-            x[u][b].load(X + (int64_t)row * a.ld, a.d, tid);
-            // The label travels with the row through the vector-memory queue.  As a scalar
-            // load it would be re-issued right before its use (scalar registers are scarce
-            // here) and put a cache miss on the dependent path of every step.
-            uint32_t row_v = row;
-            asm volatile("" : "+v"(row_v));
-            yv[u][b] = a.y[row_v];
-        }
-    };
-
-    int parity = 0;
-    auto consume = [&](int u, int64_t blk) {
-        // p_b = v.x_b and G_qb = x_q.x_b, each as NACC interleaved partial sums
-        TV acc[NR][NACC];
-#pragma unroll
-        for (int r = 0; r < NR; ++r)
-#pragma unroll
-            for (int j = 0; j < NACC; ++j) acc[r][j] = (TV)0;
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            TV xe[B];
-#pragma unroll
-            for (int b = 0; b < B; ++b) xe[b] = (TV)x[u][b].at(e);
-#pragma unroll
-            for (int b = 0; b < B; ++b) acc[b][e % NACC] += v[e] * xe[b];
-            int g = B;
-#pragma unroll
-            for (int q = 0; q < B; ++q)
-#pragma unroll
-                for (int b = q + 1; b < B; ++b) acc[g++][e % NACC] += xe[q] * xe[b];
-        }
-        TV tot[NR];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            TV t = acc[r][0];
-#pragma unroll
-            for (int j = 1; j < NACC; ++j) t += acc[r][j];
-            tot[r] = wave_sum_lane63(t);
-        }
-        if constexpr (NW > 1) {
-            if (lane == kWave - 1) {
-#pragma unroll
-                for (int r = 0; r < NR; ++r) red[parity][r][wave] = tot[r];
-            }
-            __syncthreads();
-#pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                TV t = red[parity][r][0];
-#pragma unroll
-                for (int w = 1; w < NW; ++w) t += red[parity][r][w];
-                tot[r] = t;
-            }
-            parity ^= 1;
-        } else {
-#pragma unroll
-            for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
-        }
-        // the B dependent steps, as scalars
-        TV c[B];
-#pragma unroll
-        for (int b = 0; b < B; ++b) {
-            TV dot = tot[b];
-            int g = B;
-#pragma unroll
-            for (int q = 0; q < B; ++q)
-#pragma unroll
-                for (int bb = q + 1; bb < B; ++bb) {
-                    if (bb == b) dot += c[q] * tot[g];
-                    ++g;
-                }
-            const bool live = blk * B + b < n;
-            const double s_next = live ? s * rho : s;
-            const double eos_next = live ? eta_over_s * inv_rho : 0.0;     // eta / s_next
-            if constexpr (LOSS == kLossHinge) {
-                c[b] = step_coef_hinge((double)yv[u][b], dot, s, eos_next);
-            } else {
-                c[b] = step_coef_logistic(yv[u][b], dot, (float)s, (float)eos_next);
-            }
-            if (live) {
-                s = s_next;
-                eta_over_s = eos_next;
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-#pragma unroll
-            for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
-        }
-        if (s < 0x1p-30) {          // fold the scale into v long before eta/s leaves fp32 range
-#pragma unroll
-            for (int e = 0; e < EPT; ++e) v[e] *= (TV)s;
-            s = 1.0;
-            eta_over_s = a.eta;
-        }
-    };
 
     if (n > 0) {
-        const int64_t nblk = (n + B - 1) / B;
+        uint32_t off[Frag::kChunks];               // this lane's byte offset of each chunk
 #pragma unroll
-        for (int u = 0; u < P; ++u) request(u, u);
-        int64_t blk0 = 0;
-        for (; blk0 + P <= nblk; blk0 += P) {
+        for (int c = 0; c < Frag::kChunks; ++c) off[c] = (uint32_t)(((c * NT + tid) * VEC) * sizeof(TX));
+        Frag x[P][B];
+        float yv[P][B];
+
+        // (1-eta*lambda)^lane and (1-eta*lambda)^-(lane+1), by binary powering in fp64
+        const double rho = a.rho, inv_rho = 1.0 / a.rho;
+        double rho_pow = 1.0, inv_rho_pow1 = inv_rho, rho64 = rho, inv_rho64 = inv_rho;
 #pragma unroll
-            for (int u = 0; u < P; ++u) {
-                consume(u, blk0 + u);
-                request(u, blk0 + u + P);
+        for (int bit = 0; bit < 6; ++bit) {
+            if ((lane >> bit) & 1) {
+                rho_pow *= rho64;
+                inv_rho_pow1 *= inv_rho64;
             }
+            rho64 *= rho64;
+            inv_rho64 *= inv_rho64;
         }
+        double s_w = 1.0, eos_w = a.eta;     // scale and eta/scale at the start of the window
+
+        const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
+        auto window_rows = [&](int64_t w) {
+            return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(w * kWave + lane), m32);
+        };
+        uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
+        TV zs_tab = (TV)0, cs_tab = (TV)0;   // per lane: s_l (times log2(e) for logistic), eta/s_{l+1}
+
+        // Request the B rows (and labels) of the round at in-window position j (0 <= j < 128;
+        // positions >= 64 lie in the next window) into slot u.
+        auto request = [&](int u, int j) {
 #pragma unroll
-        for (int u = 0; u < P; ++u) {
-            if (blk0 + u < nblk) consume(u, blk0 + u);
+            for (int b = 0; b < B; ++b) {
+                const int jj = j + b;
+                const uint32_t ra = (uint32_t)__builtin_amdgcn_readlane((int)rows_a, jj & (kWave - 1));
+                const uint32_t rb = (uint32_t)__builtin_amdgcn_readlane((int)rows_b, jj & (kWave - 1));
+                const uint32_t row = jj < kWave ? ra : rb;
+                const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (int64_t)row * row_stride, row_bytes);
+#pragma unroll
+                for (int c = 0; c < Frag::kChunks; ++c) x[u][b].load_chunk(c, rx, off[c]);
+                // the label rides the same queue (a scalar load would be drained at every LDS wait)
+                const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y + row, 4u);
+                yv[u][b] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(ry, 0, 0, 0));
+            }
+        };
+
+        int parity = 0;
+        // One round: steps at in-window positions j .. j+B-1, rows in slot u.  While the partial
+        // sums cross the workgroup, slot u_prev (consumed one round ago) is requested again for
+        // the round at position j_next.
+        auto round = [&](int u, int j, int u_prev, int j_next) {
+            TV acc[NR][NACC];
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int q = 0; q < NACC; ++q) acc[r][q] = (TV)0;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                TV xe[B];
+#pragma unroll
+                for (int b = 0; b < B; ++b) xe[b] = (TV)x[u][b].at(e);
+#pragma unroll
+                for (int b = 0; b < B; ++b) acc[b][e % NACC] += v[e] * xe[b];
+                int g = B;
+#pragma unroll
+                for (int q = 0; q < B; ++q)
+#pragma unroll
+                    for (int b = q + 1; b < B; ++b) acc[g++][e % NACC] += xe[q] * xe[b];
+            }
+            TV tot[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                TV t = acc[r][0];
+#pragma unroll
+                for (int q = 1; q < NACC; ++q) t += acc[r][q];
+                tot[r] = wave_sum_lane63(t);
+            }
+            if constexpr (NW > 1) {
+                if (lane == kWave - 1) {
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) red[parity][r][wave] = tot[r];
+                }
+            }
+            if constexpr (P > 1) request(u_prev, j_next);
+            // per-step scalars with the label folded in, ready before the sums arrive
+            TV zy[B], cy[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                zy[b] = lane_read(zs_tab, j + b) * (TV)yv[u][b];
+                cy[b] = lane_read(cs_tab, j + b) * (TV)yv[u][b];
+            }
+            if constexpr (NW > 1) {
+                __syncthreads();
+#pragma unroll
+                for (int r = 0; r < NR; ++r) {
+                    TV t = red[parity][r][0];
+#pragma unroll
+                    for (int w = 1; w < NW; ++w) t += red[parity][r][w];
+                    tot[r] = t;
+                }
+                parity ^= 1;
+            } else {
+#pragma unroll
+                for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
+            }
+            // the B dependent steps, as scalars
+            TV c[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                TV dot = tot[b];
+                int g = B;
+#pragma unroll
+                for (int q = 0; q < B; ++q)
+#pragma unroll
+                    for (int bb = q + 1; bb < B; ++bb) {
+                        if (bb == b) dot += c[q] * tot[g];
+                        ++g;
+                    }
+                if constexpr (LOSS == kLossHinge) {
+                    c[b] = (zy[b] * dot < 1.0) ? cy[b] : 0.0;              // -eta*g/s_next, g = -y or 0
+                } else {
+                    // -eta*g/s_next with g = -y/(1+exp(y*yhat)); exp as 2^(log2(e)*y*s*dot)
+                    c[b] = cy[b] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(zy[b] * dot));
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+#pragma unroll
+                for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
+            }
+            if constexpr (P == 1) request(u, j + B);      // a single slot: refill once it is free
+        };
+
+        // Slots 0..P-2 hold rounds 0..P-2 on entry to the loop; round r refills the slot of
+        // round r-1 with round r+P-1.
+#pragma unroll
+        for (int u = 0; u + 1 < P; ++u) request(u, u * B);
+        if constexpr (P == 1) request(0, 0);
+        // Let the first rows land before the loop starts.  With loads pending on entry, the wait
+        // in front of the loop's first use must cover the entry path too and is placed as a full
+        // drain that every iteration then pays; entering with an empty queue leaves only the
+        // partial waits of the steady state.  (gfx9 encoding: vmcnt = 0, expcnt and lgkmcnt open.)
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+
+        const int64_t nblk = (n + B - 1) / B;
+        const int64_t ngroups = (nblk + P - 1) / P;
+        int j0 = 0;                                 // in-window position of the group's first step
+        for (int64_t g = 0; g < ngroups; ++g) {
+            if (j0 == 0) {      // a new window of 64 steps begins (never in the middle of a group)
+                const int64_t w = (g * D) / kWave;
+                if (w > 0) {
+                    s_w *= rho64;
+                    eos_w *= inv_rho64;
+                    if (s_w < 0x1p-30) {    // fold the scale into v long before eta/s leaves fp32 range
+#pragma unroll
+                        for (int e = 0; e < EPT; ++e) v[e] *= (TV)s_w;
+                        s_w = 1.0;
+                        eos_w = a.eta;
+                    }
+                    rows_a = rows_b;
+                    rows_b = window_rows(w + 1);
+                }
+                const double sl = s_w * rho_pow, el = eos_w * inv_rho_pow1;
+                const bool live = w * kWave + lane < n;
+                if constexpr (LOSS == kLossHinge) {
+                    zs_tab = sl;
+                    cs_tab = live ? el : 0.0;
+                } else {
+                    zs_tab = (float)(sl * 1.4426950408889634);
+                    cs_tab = live ? (float)el : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < P; ++u)
+                round(u, j0 + u * B, (u + P - 1) % P, j0 + (u + P - 1) * B);
+            j0 = (j0 + D) & (kWave - 1);
         }
+        // scale at the chain's end: s_w covers the steps before the last window
+        const int64_t last_w = (n - 1) / kWave;
+        const int rem = (int)(n - last_w * kWave);                          // 1..64 steps in it
+        const double s_end = s_w * lane_read(rho_pow, rem - 1) * rho;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) v[e] = (TV)(s_end * (double)v[e]);
     }
 
-    float *out = a.W + (int64_t)chain * a.d;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
         const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
-        if (FULL || col < a.d) out[col] = (float)(s * (double)v[e]);
+        if (col < a.d) out[col] = (float)v[e];
     }
 }
 
@@ -252,7 +333,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 #if WPSGD_TX_BF16
 #define WPSGD_VARIANTS_VEC(V)                                                                  \
     V(64, 8, 8, 1, 8) V(64, 8, 8, 4, 2)                                                        \
-    V(256, 8, 8, 1, 8) V(256, 16, 8, 1, 8) V(256, 32, 8, 4, 2) V(256, 32, 8, 1, 4)             \
+    V(256, 8, 8, 1, 8) V(256, 16, 8, 1, 8) V(256, 32, 8, 1, 4) V(256, 32, 8, 4, 2)             \
     V(256, 8, 8, 4, 2) V(256, 16, 8, 4, 2)                                                     \
     V(1024, 16, 8, 1, 4) V(1024, 32, 8, 1, 2) V(1024, 16, 8, 2, 2)
 #if WPSGD_LOSS == 1
@@ -263,9 +344,9 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 #else
 #define WPSGD_VARIANTS_VEC(V)                                                                  \
     V(64, 4, 4, 1, 8) V(64, 4, 4, 1, 16) V(64, 4, 4, 2, 4) V(64, 4, 4, 4, 2)                   \
-    V(256, 4, 4, 1, 8) V(256, 8, 4, 1, 8) V(256, 16, 4, 4, 2) V(256, 32, 4, 1, 4)              \
-    V(256, 4, 4, 4, 2) V(256, 8, 4, 4, 2) V(256, 16, 4, 1, 8) V(256, 16, 4, 1, 4)              \
-    V(256, 16, 4, 2, 2) V(256, 16, 4, 2, 4) V(256, 16, 4, 4, 3) V(256, 32, 4, 4, 2)            \
+    V(256, 4, 4, 1, 8) V(256, 8, 4, 1, 8) V(256, 16, 4, 1, 8) V(256, 32, 4, 1, 4)              \
+    V(256, 4, 4, 4, 2) V(256, 8, 4, 4, 2) V(256, 16, 4, 4, 2) V(256, 16, 4, 1, 4)              \
+    V(256, 16, 4, 2, 2) V(256, 16, 4, 2, 4) V(256, 16, 4, 2, 8) V(256, 32, 4, 4, 2)            \
     V(512, 8, 4, 1, 8) V(512, 8, 4, 4, 2) V(512, 8, 4, 2, 4)                                   \
     V(1024, 4, 4, 1, 8) V(1024, 4, 4, 4, 2) V(1024, 4, 4, 2, 4)                                \
     V(1024, 16, 4, 1, 2) V(1024, 16, 4, 2, 1) V(1024, 32, 4, 1, 1)
@@ -292,12 +373,8 @@ hipError_t WPSGD_CAT(dense_reg_dispatch_, WPSGD_SUFFIX)(Plan &p, const ChainArgs
         p.block_steps = BB;                                                                    \
         p.prefetch = PP;                                                                       \
         if (a) {                                                                               \
-            if ((int64_t)NT * EPT == a->d)                                                     \
-                hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP, true>),  \
-                                   dim3(a->k), dim3(NT), 0, s, *a);                            \
-            else                                                                               \
-                hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP, false>), \
-                                   dim3(a->k), dim3(NT), 0, s, *a);                            \
+            hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP>),  \
+                               dim3(a->k), dim3(NT), 0, s, *a);                                \
             return hipGetLastError();                                                          \
         }                                                                                      \
         return hipSuccess;                                                                     \
