@@ -158,6 +158,25 @@ def main() -> int:
         "data_generation_s": t_gen,
     }
 
+    # What one workgroup per chain can reach at all: k workgroups streaming rows of this size
+    # with no arithmetic, times the share of that time the chains are alive.
+    if not w.is_csr and w.row_bytes() >= 4096 and w.row_bytes() % 16 == 0:
+        rows = int(min(w.n_steps.max(), 4096))
+        best = None
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            api.wpsgd_stream_rows(X, k, rows)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        stream_gbs = k * rows * w.row_bytes() / (best * 1e-3) / 1e9
+        imbalance = float(w.n_steps.mean() / max(1, w.n_steps.max()))
+        out["roofline"]["one_workgroup_per_chain_ceiling"] = {
+            "streaming_GBps": stream_gbs, "workgroups": k, "alive_fraction": imbalance,
+            "attainable_GBps": stream_gbs * imbalance, "frac_of_attainable": achieved / (stream_gbs * imbalance)}
+
     if not args.no_cpu_baseline:
         from oracle import oracle as orc
         Xo = orc.CSR(w.row_ptr, w.col_idx, w.vals, w.d) if w.is_csr else orc.Dense(w.dense)

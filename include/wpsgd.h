@@ -126,6 +126,15 @@ int wpsgd_sample_indices_device(uint64_t seed, int chain, int64_t n0, int64_t co
                                 int64_t *out_device, void *stream);
 
 /* ---- diagnostics ---- */
+/* Streaming ceiling probe (not a step of the method): `groups` workgroups of 256 threads each read
+ * `rows_per_group` rows of the dense matrix X, in the order the sample stream of chain = group index
+ * names them, with 64 to 128 KiB in flight and no arithmetic.  Timed by the caller, it tells how fast
+ * that many compute units can pull rows out of HBM, i.e. the ceiling of any kernel that gives one
+ * chain to one workgroup.  sink: DEVICE, groups*256 floats (written, content meaningless).
+ * Rows must be 16-byte aligned and a multiple of 16 bytes long, else UNSUPPORTED.             */
+int wpsgd_stream_rows(const wpsgd_matrix *X, int groups, int64_t rows_per_group, uint64_t seed,
+                      float *sink, void *stream);
+
 const char *wpsgd_strerror(int status);
 int wpsgd_last_hip_error(void);           /* hipError_t of the last failed HIP call on this thread */
 /* Writes a short description of the kernel the given problem would run (for logs and the

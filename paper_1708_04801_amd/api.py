@@ -25,6 +25,7 @@ EXPORTS = [
     "wpsgd_run_chains_workspace", "wpsgd_run_chains", "wpsgd_weights", "wpsgd_weights_rate",
     "wpsgd_benefit_margin", "wpsgd_combine_workspace", "wpsgd_combine", "wpsgd_sample_indices",
     "wpsgd_sample_indices_device", "wpsgd_strerror", "wpsgd_last_hip_error", "wpsgd_describe_plan",
+    "wpsgd_stream_rows",
 ]
 
 
@@ -77,6 +78,7 @@ def load():
     L.wpsgd_strerror.restype = ctypes.c_char_p
     L.wpsgd_last_hip_error.argtypes = []
     L.wpsgd_describe_plan.argtypes = [pm, ci, ci, pp, ctypes.c_char_p, sz]
+    L.wpsgd_stream_rows.argtypes = [pm, ci, i64, u64, vp, vp]
     _lib = L
     return L
 
@@ -252,3 +254,14 @@ def wpsgd_sample_indices_device(seed, chain, n0, count, m, device="cuda", stream
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_sample_indices_device")
     return out
+
+
+def wpsgd_stream_rows(X: Matrix, groups, rows_per_group, seed=0, stream=None) -> torch.Tensor:
+    """Streaming ceiling probe; returns the sink tensor (asynchronous, time it with events)."""
+    sink = torch.empty(int(groups) * 256, dtype=torch.float32, device=X.dense.device)
+    cm = X.c_struct()
+    rc = load().wpsgd_stream_rows(ctypes.byref(cm), int(groups), int(rows_per_group), int(seed),
+                                  sink.data_ptr(), _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_stream_rows")
+    return sink

@@ -387,6 +387,24 @@ int wpsgd_sample_indices_device(uint64_t seed, int chain, int64_t n0, int64_t co
     return e == hipSuccess ? WPSGD_OK : hip_fail(e);
 }
 
+int wpsgd_stream_rows(const wpsgd_matrix *X, int groups, int64_t rows_per_group, uint64_t seed,
+                      float *sink, void *stream)
+{
+    int rc = check_matrix(X);
+    if (rc != WPSGD_OK) return rc;
+    if (!X->dense || !sink || groups < 1 || rows_per_group < 1) return WPSGD_INVALID_ARG;
+    const int64_t elem = X->dtype == WPSGD_BF16 ? 2 : 4;
+    const int64_t row_bytes = X->d * elem;
+    // 16-byte loads: rows must start on 16-byte boundaries and be a whole number of them
+    if ((uintptr_t)X->dense % 16 != 0 || (X->ld * elem) % 16 != 0 || row_bytes % 16 != 0 ||
+        row_bytes > 0x7FFFFFFF)
+        return WPSGD_UNSUPPORTED;
+    hipError_t e = launch_stream_rows(X->dense, X->ld * elem, (uint32_t)row_bytes, (uint32_t)X->m, groups,
+                                      rows_per_group, (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32),
+                                      sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
 const char *wpsgd_strerror(int status)
 {
     switch (status) {

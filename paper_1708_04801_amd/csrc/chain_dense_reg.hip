@@ -337,7 +337,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     V(256, 8, 8, 4, 2) V(256, 16, 8, 4, 2)                                                     \
     V(1024, 16, 8, 1, 4) V(1024, 32, 8, 1, 2) V(1024, 16, 8, 2, 2)
 #if WPSGD_LOSS == 1
-#define WPSGD_VARIANTS_WIDE(V) V(1024, 64, 8, 1, 1) V(512, 128, 8, 1, 1)
+#define WPSGD_VARIANTS_WIDE(V) V(1024, 64, 8, 1, 1) V(512, 128, 8, 1, 1) V(1024, 64, 8, 1, 2) V(512, 128, 8, 1, 2)
 #else
 #define WPSGD_VARIANTS_WIDE(V)
 #endif

@@ -132,6 +132,71 @@ __global__ __launch_bounds__(kWave) void sample_rows_kernel(uint32_t seed_lo, ui
     }
 }
 
+// Streaming ceiling probe: `groups` workgroups each read `rows_per_group` rows of a dense matrix
+// in the order the sample stream of chain `blockIdx.x` names them, with 64 to 128 KiB in flight, and do
+// nothing else.  It measures how fast that many compute units can pull rows out of HBM at all,
+// which bounds any kernel that gives one chain to one workgroup.
+constexpr int kProbeThreads = 256;
+constexpr int kProbeDepth = 4;
+typedef uint32_t probe_u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(kProbeThreads) void stream_rows_kernel(const char *X, int64_t row_stride,
+                                                                    uint32_t row_bytes, uint32_t m,
+                                                                    int64_t rows_per_group,
+                                                                    uint32_t seed_lo, uint32_t seed_hi,
+                                                                    float *sink)
+{
+    constexpr int kSeg = 4;                              // load instructions per segment
+    RowWindow win;
+    win.init(seed_lo, seed_hi, blockIdx.x, m);
+    const uint32_t lane_off = threadIdx.x * 16u;
+    constexpr uint32_t kSegBytes = kSeg * kProbeThreads * 16u;      // 16 KiB
+    const uint32_t segs_per_row = (row_bytes + kSegBytes - 1) / kSegBytes;
+    const int64_t segments = rows_per_group * segs_per_row;
+    float acc = 0.0f;
+    // A row is cut into 16 KiB segments; kProbeDepth segments are in flight, each slot being
+    // consumed and re-requested in turn.
+    probe_u32x4 q[kProbeDepth][kSeg];
+    int64_t next_row = 0;
+    uint32_t next_seg = 0;
+    auto issue = [&](int u) {
+        const int64_t r = next_row < rows_per_group ? next_row : rows_per_group - 1;
+        const uint32_t row = win.get(r);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char *>(X + (int64_t)row * row_stride), 0, (int)row_bytes, 0x00020000);
+        const uint32_t base = next_seg * kSegBytes + lane_off;
+#pragma unroll
+        for (int c = 0; c < kSeg; ++c)
+            q[u][c] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, base + c * kProbeThreads * 16u, 0, 0);
+        if (++next_seg == segs_per_row) {
+            next_seg = 0;
+            ++next_row;
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < kProbeDepth; ++u) issue(u);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    for (int64_t done = 0; done < segments; done += kProbeDepth) {
+#pragma unroll
+        for (int u = 0; u < kProbeDepth; ++u) {
+#pragma unroll
+            for (int c = 0; c < kSeg; ++c) acc += __uint_as_float(q[u][c][0]);
+            issue(u);
+        }
+    }
+    sink[(int64_t)blockIdx.x * kProbeThreads + threadIdx.x] = acc;
+}
+
+hipError_t launch_stream_rows(const void *X, int64_t row_stride, uint32_t row_bytes, uint32_t m,
+                              int groups, int64_t rows_per_group, uint32_t seed_lo, uint32_t seed_hi,
+                              float *sink, hipStream_t s)
+{
+    hipLaunchKernelGGL(stream_rows_kernel, dim3(groups), dim3(kProbeThreads), 0, s,
+                       static_cast<const char *>(X), row_stride, row_bytes, m, rows_per_group, seed_lo,
+                       seed_hi, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_sample_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, int64_t n0,
                               int64_t count, uint32_t m, int64_t *out, hipStream_t s)
 {

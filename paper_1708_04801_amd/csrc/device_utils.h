@@ -49,6 +49,15 @@ __host__ __device__ inline uint32_t sample_row(uint32_t seed_lo, uint32_t seed_h
     return mul_hi_u32(r0, m);
 }
 
+// Rows of the 64 steps starting at `base`, one per lane.  Kept out of line: it runs once per 64
+// steps, and inlining its ~80 integer instructions at every use bloats the loops around it.
+__device__ __attribute__((noinline)) inline uint32_t sample_window(uint32_t seed_lo, uint32_t seed_hi,
+                                                                   uint32_t chain, int64_t base,
+                                                                   uint32_t m)
+{
+    return sample_row(seed_lo, seed_hi, chain, (uint64_t)(base + (int)(threadIdx.x & (kWave - 1))), m);
+}
+
 // One wave's window onto a chain's sample stream: lane l holds the row of step base+l.
 // get(step) must be called with a wave-uniform step; it refills the window (64 Philox
 // evaluations, one per lane) whenever the step leaves it.
@@ -68,7 +77,7 @@ struct RowWindow {
         const int64_t b = step & ~(int64_t)(kWave - 1);
         if (b != base) {
             base = b;
-            rows = sample_row(seed_lo, seed_hi, chain, (uint64_t)(b + (int)(threadIdx.x & (kWave - 1))), m);
+            rows = sample_window(seed_lo, seed_hi, chain, b, m);
         }
         return (uint32_t)__builtin_amdgcn_readlane((int)rows, (int)(step & (kWave - 1)));
     }
@@ -87,17 +96,28 @@ struct RowWindow {
 // then bcast31 into rows 2 and 3, leaves the wave total in row 3, i.e. in lane 63.
 // ---------------------------------------------------------------------------------------------
 template <int CTRL, int ROW_MASK>
+__device__ inline int dpp_move_bits(int x)
+{
+    if constexpr (ROW_MASK == 0xF) {
+        // every lane has a valid source for the in-row controls: no fill value is needed
+        return __builtin_amdgcn_mov_dpp(x, CTRL, 0xF, 0xF, true);
+    } else {
+        return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xF, false);
+    }
+}
+
+template <int CTRL, int ROW_MASK>
 __device__ inline float dpp_move(float x)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xF, false));
+    return __int_as_float(dpp_move_bits<CTRL, ROW_MASK>(__float_as_int(x)));
 }
 
 template <int CTRL, int ROW_MASK>
 __device__ inline double dpp_move(double x)
 {
     const long long bits = __double_as_longlong(x);
-    const int lo = __builtin_amdgcn_update_dpp(0, (int)(bits & 0xFFFFFFFFLL), CTRL, ROW_MASK, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, ROW_MASK, 0xF, false);
+    const int lo = dpp_move_bits<CTRL, ROW_MASK>((int)(bits & 0xFFFFFFFFLL));
+    const int hi = dpp_move_bits<CTRL, ROW_MASK>((int)(bits >> 32));
     return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
 }
 
