@@ -153,27 +153,48 @@ static size_t header_bytes(int k)
     return align256((size_t)k * sizeof(int32_t)) + align256((size_t)k * sizeof(int64_t));
 }
 
-// Frees a host staging buffer once the stream has consumed it.
-static void free_staging(void *p) { std::free(p); }
+// Host arrays (chain order, step counts, weights) reach the device through a small ring of pinned
+// staging buffers per host thread.  An event marks the last copy out of a buffer; it is rewritten
+// only after that copy has finished, so the caller's arrays can be released as soon as a call returns.
+struct StagingSlot {
+    void *host = nullptr;
+    size_t capacity = 0;
+    hipEvent_t last_copy = nullptr;
+    bool pending = false;
+};
+constexpr int kStagingSlots = 4;     // copies that may be queued before a call has to wait
+static thread_local StagingSlot g_staging[kStagingSlots];
+static thread_local int g_staging_next = 0;
 
 static int upload(void *dst, const void *src, size_t bytes, hipStream_t s)
 {
-    // The source must outlive the asynchronous copy: stage it in a heap block that a host
-    // callback on the same stream releases.
-    void *stage = std::malloc(bytes);
-    if (!stage) return WPSGD_INVALID_ARG;
-    std::memcpy(stage, src, bytes);
-    hipError_t e = hipMemcpyAsync(dst, stage, bytes, hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) {
-        std::free(stage);
-        return hip_fail(e);
+    StagingSlot &st = g_staging[g_staging_next];
+    g_staging_next = (g_staging_next + 1) % kStagingSlots;
+    hipError_t e;
+    if (st.pending) {
+        e = hipEventSynchronize(st.last_copy);
+        if (e != hipSuccess) return hip_fail(e);
+        st.pending = false;
     }
-    e = hipLaunchHostFunc(s, free_staging, stage);
-    if (e != hipSuccess) {
-        (void)hipStreamSynchronize(s);
-        std::free(stage);
-        return hip_fail(e);
+    if (st.capacity < bytes) {
+        if (st.host) (void)hipHostFree(st.host);
+        st.host = nullptr;
+        st.capacity = 0;
+        const size_t want = std::max<size_t>(bytes, 1 << 16);
+        e = hipHostMalloc(&st.host, want, hipHostMallocDefault);
+        if (e != hipSuccess) return hip_fail(e);
+        st.capacity = want;
     }
+    if (!st.last_copy) {
+        e = hipEventCreateWithFlags(&st.last_copy, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    std::memcpy(st.host, src, bytes);
+    e = hipMemcpyAsync(dst, st.host, bytes, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventRecord(st.last_copy, s);
+    if (e != hipSuccess) return hip_fail(e);
+    st.pending = true;
     return WPSGD_OK;
 }
 
@@ -248,21 +269,23 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
     if (workspace_bytes < need) return WPSGD_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    // longest chain first (stable, so equal lengths keep their order)
+    // longest chain first (stable, so equal lengths keep their order); order and step counts
+    // travel in one copy, laid out exactly as the workspace header
     std::vector<int32_t> order(k);
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
                      [&](int32_t x, int32_t z) { return n_steps[x] > n_steps[z]; });
-    std::vector<int64_t> sorted_steps(k);
+    const size_t order_bytes = align256((size_t)k * sizeof(int32_t));
+    std::vector<char> header(header_bytes(k), 0);
+    std::memcpy(header.data(), order.data(), (size_t)k * sizeof(int32_t));
+    int64_t *sorted_steps = reinterpret_cast<int64_t *>(header.data() + order_bytes);
     for (int b = 0; b < k; ++b) sorted_steps[b] = n_steps[order[b]];
 
     char *ws = static_cast<char *>(workspace);
     int32_t *order_dev = reinterpret_cast<int32_t *>(ws);
-    int64_t *steps_dev = reinterpret_cast<int64_t *>(ws + align256((size_t)k * sizeof(int32_t)));
+    int64_t *steps_dev = reinterpret_cast<int64_t *>(ws + order_bytes);
     void *state_dev = ws + header_bytes(k);
-    rc = upload(order_dev, order.data(), (size_t)k * sizeof(int32_t), s);
-    if (rc != WPSGD_OK) return rc;
-    rc = upload(steps_dev, sorted_steps.data(), (size_t)k * sizeof(int64_t), s);
+    rc = upload(ws, header.data(), header.size(), s);
     if (rc != WPSGD_OK) return rc;
 
     ChainArgs a{};

@@ -318,29 +318,161 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     }
 }
 
+// Wide rows: the model vector still lives in registers (1024 threads x EPT elements), but a row
+// no longer fits beside it, so a step streams its row twice and keeps none of it: the first
+// pass (from HBM) forms v.x, the second (the row is then in L2) applies v += c*x.  Same
+// recursion, same per-window scalar tables, one step per round.
+template <typename TX, int LOSS, int NT, int EPT, int VEC>
+__global__ __launch_bounds__(NT) void chain_dense_wide_kernel(ChainArgs a)
+{
+    using TV = typename StateType<LOSS>::type;
+    using Frag = RowFrag<TX, NT, VEC, VEC>;        // one chunk: VEC elements
+    constexpr int NW = NT / kWave;
+    constexpr int CHUNKS = EPT / VEC;
+    constexpr int GROUP = CHUNKS >= 4 ? 4 : CHUNKS;    // chunks requested together
+    constexpr int NGROUPS = CHUNKS / GROUP;
+    static_assert(CHUNKS % GROUP == 0, "whole groups");
+    __shared__ TV red[2][NW];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int chain = a.order[blockIdx.x];
+    const int64_t n = a.nsteps[blockIdx.x];
+    const char *X = static_cast<const char *>(a.dense);
+    const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
+    const uint32_t row_bytes = (uint32_t)(a.d * (int64_t)sizeof(TX));
+    float *out = a.W + (int64_t)chain * a.d;
+
+    TV v[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) v[e] = (TV)0;
+
+    if (n > 0) {
+        const uint32_t off0 = (uint32_t)((tid * VEC) * sizeof(TX));          // chunk c adds c*NT*VEC elements
+        constexpr uint32_t kChunkStride = (uint32_t)(NT * VEC * sizeof(TX));
+        const double rho = a.rho, inv_rho = 1.0 / a.rho;
+        double rho_pow = 1.0, inv_rho_pow1 = inv_rho, rho64 = rho, inv_rho64 = inv_rho;
+#pragma unroll
+        for (int bit = 0; bit < 6; ++bit) {
+            if ((lane >> bit) & 1) {
+                rho_pow *= rho64;
+                inv_rho_pow1 *= inv_rho64;
+            }
+            rho64 *= rho64;
+            inv_rho64 *= inv_rho64;
+        }
+        double s_w = 1.0, eos_w = a.eta;
+        uint32_t rows = 0;
+        TV zs_tab = (TV)0, cs_tab = (TV)0;
+        int parity = 0;
+
+        // Streams the row behind rx through f(e, x_e), GROUP chunks in flight ahead of their use.
+        auto stream_row = [&](__amdgpu_buffer_rsrc_t rx, auto &&f) {
+            Frag buf[2][GROUP];
+#pragma unroll
+            for (int c = 0; c < GROUP; ++c) buf[0][c].load_chunk(0, rx, off0 + c * kChunkStride);
+#pragma unroll
+            for (int g = 0; g < NGROUPS; ++g) {
+                if (g + 1 < NGROUPS) {
+#pragma unroll
+                    for (int c = 0; c < GROUP; ++c)
+                        buf[(g + 1) & 1][c].load_chunk(0, rx, off0 + ((g + 1) * GROUP + c) * kChunkStride);
+                }
+#pragma unroll
+                for (int c = 0; c < GROUP; ++c)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) f((g * GROUP + c) * VEC + i, buf[g & 1][c].at(i));
+            }
+        };
+
+        for (int64_t step = 0; step < n; ++step) {
+            const int j = (int)(step & (kWave - 1));
+            if (j == 0) {       // a new window of 64 steps
+                if (step > 0) {
+                    s_w *= rho64;
+                    eos_w *= inv_rho64;
+                    if (s_w < 0x1p-30) {
+#pragma unroll
+                        for (int e = 0; e < EPT; ++e) v[e] *= (TV)s_w;
+                        s_w = 1.0;
+                        eos_w = a.eta;
+                    }
+                }
+                rows = sample_window(a.seed_lo, a.seed_hi, (uint32_t)chain, step, (uint32_t)a.m);
+                const double sl = s_w * rho_pow, el = eos_w * inv_rho_pow1;
+                if constexpr (LOSS == kLossHinge) {
+                    zs_tab = sl;
+                    cs_tab = el;
+                } else {
+                    zs_tab = (float)(sl * 1.4426950408889634);
+                    cs_tab = (float)el;
+                }
+            }
+            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)rows, j);
+            const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (int64_t)row * row_stride, row_bytes);
+            const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y + row, 4u);
+            const TV y = (TV)__uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(ry, 0, 0, 0));
+
+            TV acc[4] = {(TV)0, (TV)0, (TV)0, (TV)0};
+            stream_row(rx, [&](int e, float xe) { acc[e & 3] += v[e] * (TV)xe; });
+            TV tot = wave_sum_lane63((acc[0] + acc[1]) + (acc[2] + acc[3]));
+            if (lane == kWave - 1) red[parity][wave] = tot;
+            const TV zy = lane_read(zs_tab, j) * y, cy = lane_read(cs_tab, j) * y;
+            __syncthreads();
+            tot = red[parity][0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) tot += red[parity][w];
+            parity ^= 1;
+            TV c;
+            if constexpr (LOSS == kLossHinge) {
+                c = (zy * tot < 1.0) ? cy : 0.0;
+            } else {
+                c = cy * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(zy * tot));
+            }
+            if (c != (TV)0)      // uniform: every thread holds the same c
+                stream_row(rx, [&](int e, float xe) { v[e] += c * (TV)xe; });
+        }
+        const int64_t last_w = (n - 1) / kWave;
+        const int rem = (int)(n - last_w * kWave);
+        const double s_end = s_w * lane_read(rho_pow, rem - 1) * rho;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) v[e] = (TV)(s_end * (double)v[e]);
+    }
+
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
+        if (col < a.d) out[col] = (float)v[e];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Instantiated variants: V(threads, elements per thread, load width, B, P).  Within one
 // (threads, ept, vec) shape the first entry is the default; the others are reachable through a
 // forced plan.  Register budget per thread: 512 at 256 threads, 256 at 512, 128 at 1024.
 // ---------------------------------------------------------------------------------------------
+// 64 elements per thread only with fp32 state (logistic): 64 fp64 values would fill the registers
+#if WPSGD_LOSS == 1
+#define WPSGD_WIDEST(V, VEC) V(1024, 64, VEC, 1, 0)
+#else
+#define WPSGD_WIDEST(V, VEC)
+#endif
+
 #define WPSGD_VARIANTS_ANY(V)                                                                  \
     V(64, 1, 1, 1, 8) V(64, 2, 1, 1, 8) V(64, 4, 1, 1, 8)                                      \
     V(64, 1, 1, 4, 2) V(64, 4, 1, 2, 4)                                                        \
     V(256, 4, 1, 1, 4) V(256, 8, 1, 1, 4) V(256, 16, 1, 1, 4) V(256, 32, 1, 1, 2)              \
     V(256, 4, 1, 4, 2) V(256, 16, 1, 4, 2)                                                     \
-    V(1024, 16, 1, 1, 2) V(1024, 32, 1, 1, 1)
+    V(1024, 16, 1, 1, 0) V(1024, 32, 1, 1, 0) WPSGD_WIDEST(V, 1)
 
 #if WPSGD_TX_BF16
 #define WPSGD_VARIANTS_VEC(V)                                                                  \
     V(64, 8, 8, 1, 8) V(64, 8, 8, 4, 2)                                                        \
     V(256, 8, 8, 1, 8) V(256, 16, 8, 1, 8) V(256, 32, 8, 1, 4) V(256, 32, 8, 4, 2)             \
     V(256, 8, 8, 4, 2) V(256, 16, 8, 4, 2)                                                     \
-    V(1024, 16, 8, 1, 4) V(1024, 32, 8, 1, 2) V(1024, 16, 8, 2, 2)
-#if WPSGD_LOSS == 1
-#define WPSGD_VARIANTS_WIDE(V) V(1024, 64, 8, 1, 1) V(512, 128, 8, 1, 1) V(1024, 64, 8, 1, 2) V(512, 128, 8, 1, 2)
-#else
+    V(1024, 16, 8, 1, 0) V(1024, 32, 8, 1, 0) WPSGD_WIDEST(V, 8)
 #define WPSGD_VARIANTS_WIDE(V)
-#endif
 #else
 #define WPSGD_VARIANTS_VEC(V)                                                                  \
     V(64, 4, 4, 1, 8) V(64, 4, 4, 1, 16) V(64, 4, 4, 2, 4) V(64, 4, 4, 4, 2)                   \
@@ -349,11 +481,22 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     V(256, 16, 4, 2, 2) V(256, 16, 4, 2, 4) V(256, 16, 4, 2, 8) V(256, 32, 4, 4, 2)            \
     V(512, 8, 4, 1, 8) V(512, 8, 4, 4, 2) V(512, 8, 4, 2, 4)                                   \
     V(1024, 4, 4, 1, 8) V(1024, 4, 4, 4, 2) V(1024, 4, 4, 2, 4)                                \
-    V(1024, 16, 4, 1, 2) V(1024, 16, 4, 2, 1) V(1024, 32, 4, 1, 1)
+    V(1024, 16, 4, 1, 0) V(1024, 32, 4, 1, 0) WPSGD_WIDEST(V, 4)
 #define WPSGD_VARIANTS_WIDE(V)
 #endif
 
 #define WPSGD_ALL_VARIANTS(V) WPSGD_VARIANTS_VEC(V) WPSGD_VARIANTS_ANY(V) WPSGD_VARIANTS_WIDE(V)
+
+// P == 0 marks the wide kernel (rows streamed, not held in registers)
+template <int NT, int EPT, int VEC, int BB, int PP>
+static void launch_variant(const ChainArgs &a, hipStream_t s)
+{
+    if constexpr (PP == 0) {
+        hipLaunchKernelGGL((chain_dense_wide_kernel<RowElem, kLoss, NT, EPT, VEC>), dim3(a.k), dim3(NT), 0, s, a);
+    } else {
+        hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP>), dim3(a.k), dim3(NT), 0, s, a);
+    }
+}
 
 #define WPSGD_CAT2(a, b) a##b
 #define WPSGD_CAT(a, b) WPSGD_CAT2(a, b)
@@ -369,12 +512,11 @@ hipError_t WPSGD_CAT(dense_reg_dispatch_, WPSGD_SUFFIX)(Plan &p, const ChainArgs
 {
 #define WPSGD_TRY(NT, EPT, VEC, BB, PP)                                                        \
     if (p.threads == NT && p.ept == EPT && p.vec == VEC && (p.block_steps == 0 || p.block_steps == BB) && \
-        (p.prefetch == 0 || p.prefetch == PP)) {                                               \
+        (p.prefetch == 0 || p.prefetch == PP || PP == 0)) {                                               \
         p.block_steps = BB;                                                                    \
         p.prefetch = PP;                                                                       \
         if (a) {                                                                               \
-            hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP>),  \
-                               dim3(a->k), dim3(NT), 0, s, *a);                                \
+            launch_variant<NT, EPT, VEC, BB, PP>(*a, s);                                        \
             return hipGetLastError();                                                          \
         }                                                                                      \
         return hipSuccess;                                                                     \
