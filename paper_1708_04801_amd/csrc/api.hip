@@ -73,7 +73,7 @@ static int dense_vec(const wpsgd_matrix *X)
 // Chooses the kernel family and its parameters.  Dense rows go to the register kernel when
 // some instantiated shape holds d elements, else to the HBM-state kernel.
 static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan *force, Plan *out,
-                        double rho = 1.0)
+                        double rho = 1.0, int64_t max_steps = 0)
 {
     Plan p{};
     p.loss = (int)loss;
@@ -84,12 +84,17 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
 
     if (!X->dense) {
         if (f.threads && f.threads != kWave) return WPSGD_UNSUPPORTED;
-        if (f.block_steps > 1 || f.prefetch > 1) return WPSGD_UNSUPPORTED;
+        if (f.block_steps > 1 || (f.prefetch > 1 && f.prefetch != 4)) return WPSGD_UNSUPPORTED;
         p.family = Family::Csr;
         p.threads = kWave;
         p.vec = 1;
         p.block_steps = 1;
-        p.prefetch = 1;
+        // The LDS-cached kernel (prefetch 4) never folds its lazy scale back into the vector, so
+        // it needs (1-eta*lambda)^steps to stay well inside fp32 range, and 64 columns of scratch.
+        const bool no_fold = (double)max_steps * std::log(rho) > -55.0;       // scale > 2^-80
+        const bool cached_ok = X->d >= 64 && no_fold;
+        if (f.prefetch == 4 && !cached_ok) return WPSGD_UNSUPPORTED;
+        p.prefetch = (f.prefetch == 1 || !cached_ok) ? 1 : 4;
         p.state_bytes_per_elem = state_elem;
         *out = p;
         return WPSGD_OK;
@@ -262,7 +267,9 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
     if (!(eta > 0.0) || !(lambda >= 0.0) || !(eta * lambda < 1.0)) return WPSGD_INVALID_ARG;
     if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
     Plan p;
-    rc = resolve_plan(X, loss, plan, &p, 1.0 - eta * lambda);
+    int64_t max_steps = 0;
+    for (int i = 0; i < k; ++i) max_steps = std::max(max_steps, n_steps[i]);
+    rc = resolve_plan(X, loss, plan, &p, 1.0 - eta * lambda, max_steps);
     if (rc != WPSGD_OK) return rc;
     const size_t need = header_bytes(k) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
     if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;

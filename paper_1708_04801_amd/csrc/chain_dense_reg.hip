@@ -84,19 +84,6 @@ struct RowFrag {
     }
 };
 
-// Wave-uniform read of lane j of a per-lane table.
-__device__ inline float lane_read(float t, int j)
-{
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), j));
-}
-__device__ inline double lane_read(double t, int j)
-{
-    const long long bits = __double_as_longlong(t);
-    const int lo = __builtin_amdgcn_readlane((int)(bits & 0xFFFFFFFFLL), j);
-    const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), j);
-    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
-}
-
 // TX and LOSS are template parameters (not just per-file constants) so that the four builds of
 // this file produce four distinct sets of kernel symbols.
 template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P>

@@ -154,6 +154,22 @@ __device__ inline T wave_sum(T v)
     return read_lane63(wave_sum_lane63(v));
 }
 
+// Wave-uniform read of lane j of a per-lane value.
+__device__ inline float lane_read(float t, int j)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), j));
+}
+__device__ inline int64_t lane_read_i64(int64_t t, int j)
+{
+    const int lo = __builtin_amdgcn_readlane((int)(t & 0xFFFFFFFFLL), j);
+    const int hi = __builtin_amdgcn_readlane((int)(t >> 32), j);
+    return ((int64_t)hi << 32) | (int64_t)(unsigned int)lo;
+}
+__device__ inline double lane_read(double t, int j)
+{
+    return __longlong_as_double(lane_read_i64(__double_as_longlong(t), j));
+}
+
 // bfloat16 is the upper half of a binary32: widening is a shift.
 __device__ inline float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ inline float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xFFFF0000u); }

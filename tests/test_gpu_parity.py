@@ -231,17 +231,55 @@ def test_many_more_chains_than_compute_units():
 
 # ------------------------------------------------------------------ CSR chains
 
+@pytest.mark.parametrize("plan", [None, {"prefetch": 1}])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
-def test_sparse_chains_small(loss):
+def test_sparse_chains_small(loss, plan):
+    """plan None: head columns in LDS, tail values prefetched; prefetch 1: the plain kernel."""
     w = wl.sparse_hinge(m=5000, d=1 << 14, k=12, n_median=300)
     w.loss = loss
     w.n_steps[3] = 0
-    check_against_oracle(w, gpu_chains(w), label="sparse small")
+    w.n_steps[5] = 1
+    X = api.matrix_from_workload(w)
+    desc = api.wpsgd_describe_plan(X, w.k, loss, plan)
+    assert ("P=4" in desc) == (plan is None)
+    W = gpu_chains(w, plan=plan, X=X)
+    check_against_oracle(w, W, label=f"sparse small [{desc}]")
+    assert torch.equal(W, gpu_chains(w, plan=plan, X=X))
+
+
+def test_sparse_tail_conflicts_are_caught():
+    """Few tail columns and many steps: consecutive steps keep writing the columns the next
+    ones have already fetched, so the stale-value check has to fire all the time."""
+    rng = np.random.default_rng(45)
+    m, d = 300, 8192 + 40                       # 40 columns beyond the LDS-resident head
+    rp, ci, va = [0], [], []
+    for r in range(m):
+        head = np.sort(rng.choice(8192, size=20, replace=False))
+        tail = 8192 + np.sort(rng.choice(40, size=6, replace=False))
+        c = np.concatenate([head, tail])
+        v = rng.standard_normal(c.size)
+        v /= np.linalg.norm(v)
+        ci += c.tolist()
+        va += v.tolist()
+        rp.append(len(ci))
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    for loss in (wl.HINGE, wl.LOGISTIC):
+        w = wl.Workload("tail_conflicts", loss, 0.3, 1e-4, 9, np.array([900, 257, 64, 3], dtype=np.int64), y, m, d,
+                        row_ptr=np.array(rp, dtype=np.int64), col_idx=np.array(ci, dtype=np.int32),
+                        vals=np.array(va, dtype=np.float32))
+        check_against_oracle(w, gpu_chains(w), label="tail conflicts")
+
+
+def test_sparse_heavy_shrink_takes_the_plain_kernel():
+    w = wl.sparse_hinge(m=2000, d=1 << 13, k=4, n_median=400)
+    w.eta, w.lam = 0.5, 0.6                      # rate 0.7: the lazy scale must be folded
+    X = api.matrix_from_workload(w)
+    check_against_oracle(w, gpu_chains(w, X=X), label="sparse heavy shrink")
 
 
 def test_sparse_rows_longer_than_the_register_window():
     rng = np.random.default_rng(44)
-    m, d = 40, 5000
+    m, d = 40, 20000
     rp, ci, va = [0], [], []
     for r in range(m):
         nnz = [1, 64, 65, 256, 257, 700][r % 6]
