@@ -66,6 +66,10 @@ typedef struct wpsgd_plan {
     int block_steps;     /* SGD steps folded into one reduction round: 1, 2, 4 or 8             */
     int prefetch;        /* rounds of sample rows kept in flight ahead of the one being consumed */
     int state_in_hbm;    /* 1: keep the model vector in the workspace (HBM) instead of registers */
+    int rows;            /* where a dense row waits between its dot product and its update:
+                            1 registers, requested `prefetch` rounds ahead; 2 registers, with the next
+                            row landing in LDS meanwhile (rows up to 128 KiB); 3 nowhere: the row is
+                            streamed twice (rows too long for 1 and 2)                               */
 } wpsgd_plan;
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----

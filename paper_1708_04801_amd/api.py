@@ -37,7 +37,8 @@ class _CMatrix(ctypes.Structure):
 
 class _CPlan(ctypes.Structure):
     _fields_ = [("threads", ctypes.c_int), ("block_steps", ctypes.c_int),
-                ("prefetch", ctypes.c_int), ("state_in_hbm", ctypes.c_int)]
+                ("prefetch", ctypes.c_int), ("state_in_hbm", ctypes.c_int),
+                ("rows", ctypes.c_int)]
 
 
 class WpsgdError(RuntimeError):
@@ -133,6 +134,7 @@ def _plan(plan):
     p.block_steps = int(plan.get("block_steps", 0))
     p.prefetch = int(plan.get("prefetch", 0))
     p.state_in_hbm = int(plan.get("state_in_hbm", 0))
+    p.rows = int(plan.get("rows", 0))
     return ctypes.byref(p)
 
 

@@ -25,7 +25,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed-fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument", "-Wno-ignored-attributes",
+    "-Wno-unused-command-line-argument", "-Wno-ignored-attributes", "-Wno-inline-asm",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 

@@ -79,12 +79,12 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
     p.loss = (int)loss;
     p.dtype = X->dense ? (int)X->dtype : WPSGD_F32;
     const size_t state_elem = (loss == WPSGD_HINGE) ? sizeof(double) : sizeof(float);
-    const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0};
-    if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0) return WPSGD_INVALID_ARG;
+    const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0, 0};
+    if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0 || f.rows < 0 || f.rows > 3) return WPSGD_INVALID_ARG;
 
     if (!X->dense) {
         if (f.threads && f.threads != kWave) return WPSGD_UNSUPPORTED;
-        if (f.block_steps > 1 || (f.prefetch > 1 && f.prefetch != 4)) return WPSGD_UNSUPPORTED;
+        if (f.block_steps > 1 || (f.prefetch > 1 && f.prefetch != 4) || f.rows) return WPSGD_UNSUPPORTED;
         p.family = Family::Csr;
         p.threads = kWave;
         p.vec = 1;
@@ -126,6 +126,7 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
                 q.ept = ept;
                 q.block_steps = f.block_steps;
                 q.prefetch = f.prefetch;
+                q.rows = f.rows;
                 q.state_bytes_per_elem = 0;
                 if (dense_reg_dispatch(q, nullptr, nullptr) == hipSuccess) {
                     *out = q;
@@ -133,8 +134,9 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
                 }
             }
         }
-        if (f.threads || f.block_steps || f.prefetch) return WPSGD_UNSUPPORTED;
+        if (f.threads || f.block_steps || f.prefetch || f.rows) return WPSGD_UNSUPPORTED;
     }
+    if (f.rows) return WPSGD_UNSUPPORTED;
     p.family = Family::DenseMem;
     p.threads = f.threads ? f.threads : (X->d >= 16384 ? 1024 : 256);
     if (p.threads != 256 && p.threads != 1024) return WPSGD_UNSUPPORTED;
@@ -247,11 +249,13 @@ int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     Plan p;
     rc = resolve_plan(X, loss, plan, &p);
     if (rc != WPSGD_OK) return rc;
-    std::snprintf(buf, buf_bytes, "%s %s %s nt=%d ept=%d vec=%d B=%d P=%d state=%s",
+    static const char *const kRows[] = {"", " rows=registers", " rows=lds", " rows=twice"};
+    std::snprintf(buf, buf_bytes, "%s %s %s nt=%d ept=%d vec=%d B=%d P=%d state=%s%s",
                   family_name(p.family), p.dtype == WPSGD_BF16 ? "bf16" : "f32",
                   p.loss == WPSGD_HINGE ? "hinge" : "logistic", p.threads, p.ept, p.vec,
                   p.block_steps, p.prefetch,
-                  p.state_bytes_per_elem == 0 ? "registers" : (p.state_bytes_per_elem == 8 ? "hbm-f64" : "hbm-f32"));
+                  p.state_bytes_per_elem == 0 ? "registers" : (p.state_bytes_per_elem == 8 ? "hbm-f64" : "hbm-f32"),
+                  p.family == Family::DenseReg ? kRows[p.rows] : "");
     return WPSGD_OK;
 }
 

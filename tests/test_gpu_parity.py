@@ -129,6 +129,10 @@ DENSE_PLANS = [
     (4096, wl.LOGISTIC, {"state_in_hbm": 1}), (300, wl.HINGE, {"state_in_hbm": 1}),
     (5001, wl.HINGE, {"state_in_hbm": 1}), (20000, wl.LOGISTIC, {"state_in_hbm": 1, "threads": 1024}),
     (70000, wl.LOGISTIC, None), (40000, wl.HINGE, None),
+    # long rows: next row staged in LDS (the default up to 128 KiB) or streamed twice
+    (12000, wl.LOGISTIC, {"rows": 3}), (16384, wl.HINGE, {"rows": 3}), (20000, wl.LOGISTIC, {"rows": 3}),
+    (20000, wl.HINGE, {"rows": 2}), (32768, wl.LOGISTIC, {"rows": 2}), (32768, wl.HINGE, None),
+    (40000, wl.LOGISTIC, None),
 ]
 
 
@@ -143,6 +147,8 @@ def test_dense_fp32_chains(d, loss, plan):
     w = wl.Workload("dense_small", loss, 0.5 if loss == wl.HINGE else 2.0, 1e-3, 11, n, y, m, d, dense=X)
     Xg = api.matrix_from_workload(w)
     desc = api.wpsgd_describe_plan(Xg, k, loss, plan)
+    if plan and "rows" in plan:
+        assert ("rows=lds" if plan["rows"] == 2 else "rows=twice") in desc
     W = gpu_chains(w, plan=plan, X=Xg)
     check_against_oracle(w, W, label=f"d={d} [{desc}]")
     assert (W[2] == 0).all()                                     # idle chain keeps w_0 = 0
@@ -152,7 +158,8 @@ def test_dense_fp32_chains(d, loss, plan):
 
 BF16_PLANS = [(64, None), (256, None), (512, None), (520, None), (2048, {"block_steps": 4}), (4096, None),
               (8192, {"block_steps": 1}), (16384, None), (30000, None), (65536, None),
-              (65536, {"state_in_hbm": 1}), (4100, {"state_in_hbm": 1}), (40000, None), (33000, None)]
+              (65536, {"state_in_hbm": 1}), (4100, {"state_in_hbm": 1}), (40000, None), (33000, None),
+              (16384, {"rows": 3}), (30000, {"rows": 3}), (12000, {"rows": 2})]
 
 
 @pytest.mark.parametrize("d,plan", BF16_PLANS)
@@ -169,6 +176,24 @@ def test_dense_bf16_chains(d, plan, loss):
     Xg = api.matrix_from_workload(w)
     desc = api.wpsgd_describe_plan(Xg, 4, loss, plan)
     check_against_oracle(w, gpu_chains(w, plan=plan, X=Xg), label=f"bf16 d={d} [{desc}]")
+
+
+def test_widest_bf16_rows_both_ways():
+    """d = 65536 in bfloat16 (128 KiB rows): the LDS-staged kernel is the default, the kernel that
+    streams every row twice stays reachable; both must match the oracle and each other closely."""
+    rng = np.random.default_rng(77)
+    m, d = 80, 65536
+    bits = wl.f32_to_bf16_bits((rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32))
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = np.array([200, 65, 1, 0, 64], dtype=np.int64)
+    w = wl.Workload("bf16_widest", wl.LOGISTIC, 0.5, 1e-3, 5, n, y, m, d, dense=bits)
+    Xg = api.matrix_from_workload(w)
+    assert "rows=lds" in api.wpsgd_describe_plan(Xg, 5, wl.LOGISTIC)
+    assert "rows=twice" in api.wpsgd_describe_plan(Xg, 5, wl.LOGISTIC, {"rows": 3})
+    for plan in (None, {"rows": 3}):
+        W = gpu_chains(w, plan=plan, X=Xg)
+        check_against_oracle(w, W, label=f"bf16 widest {plan}")
+        assert torch.equal(W, gpu_chains(w, plan=plan, X=Xg))
 
 
 def test_dense_rows_with_padding_and_misaligned_base():
