@@ -83,18 +83,23 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
     if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0 || f.rows < 0 || f.rows > 3) return WPSGD_INVALID_ARG;
 
     if (!X->dense) {
-        if (f.threads && f.threads != kWave) return WPSGD_UNSUPPORTED;
-        if (f.block_steps > 1 || (f.prefetch > 1 && f.prefetch != 4) || f.rows) return WPSGD_UNSUPPORTED;
+        if (f.threads && f.threads != kWave && f.threads != 2 * kWave) return WPSGD_UNSUPPORTED;
+        if (f.block_steps > 1 || (f.prefetch > 1 && f.prefetch != 4 && f.prefetch != 8) || f.rows) return WPSGD_UNSUPPORTED;
         p.family = Family::Csr;
         p.threads = kWave;
         p.vec = 1;
         p.block_steps = 1;
-        // The LDS-cached kernel (prefetch 4) never folds its lazy scale back into the vector, so
-        // it needs (1-eta*lambda)^steps to stay well inside fp32 range, and 64 columns of scratch.
+        // The LDS-cached kernels (prefetch 4: one wave per chain, 8: two) never fold their lazy scale
+        // back into the vector, so they need (1-eta*lambda)^steps to stay well inside fp32 range.
+        // They park unused lanes on scratch columns at the start of the vector, and the two-wave
+        // kernel addresses the vector with 32-bit byte offsets.
         const bool no_fold = (double)max_steps * std::log(rho) > -55.0;       // scale > 2^-80
         const bool cached_ok = X->d >= 64 && no_fold;
+        const bool pair_ok = X->d >= 128 && no_fold && (uint64_t)X->d * state_elem < (1ull << 32);
         if (f.prefetch == 4 && !cached_ok) return WPSGD_UNSUPPORTED;
-        p.prefetch = (f.prefetch == 1 || !cached_ok) ? 1 : 4;
+        if (f.prefetch == 8 && !pair_ok) return WPSGD_UNSUPPORTED;
+        p.prefetch = f.prefetch ? f.prefetch : (pair_ok ? 8 : (cached_ok ? 4 : 1));
+        if (p.prefetch == 8) p.threads = 2 * kWave;
         p.state_bytes_per_elem = state_elem;
         *out = p;
         return WPSGD_OK;

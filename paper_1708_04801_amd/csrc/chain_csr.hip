@@ -86,10 +86,11 @@ __global__ __launch_bounds__(kWave) void chain_csr_kernel(ChainArgs a)
 //  * The other columns stay in HBM.  The rows a chain visits are known ahead of time, so their
 //    entries (column, value) are requested 2Q steps ahead and the model values at their tail
 //    columns Q steps ahead; both wait in registers.  A value fetched early is stale if one of
-//    the steps in between wrote the same column.  Every tail write leaves the step number in a
-//    small LDS table indexed by the column's low bits; a step whose tail columns find a recent
-//    step number there (a real conflict or a harmless alias) drains the memory queue and reads
-//    its tail values again.  No false negatives: a write always leaves its stamp.
+//    the steps in between wrote the same column.  Every tail write leaves the step number in
+//    two small LDS tables, indexed by two different hashes of the column; a step whose tail
+//    column finds a recent step number in both (a real conflict, or - rarely - two unrelated
+//    aliases at once) drains the memory queue and reads its tail values again.  No false
+//    negatives: a write always leaves both stamps.
 //  * Nothing in the loop is conditional on data except that re-read, which is written with
 //    inline memory instructions so that the compiler's count of outstanding loads - and with it
 //    the partial waits that keep the prefetch alive - is the same on both paths.
@@ -98,10 +99,11 @@ __global__ __launch_bounds__(kWave) void chain_csr_kernel(ChainArgs a)
 // entry loads of step t+2Q are issued after the stores of step t and are waited for at step
 // t+Q (when the tail values of step t+2Q are requested), so at any step i all stores of steps
 // <= i-Q are complete, and a tail value requested at step i for step i+Q can only miss writes
-// of steps i-Q+1 .. i+Q-1.  The stamp test covers the last 3Q steps.
+// of steps i-Q+1 .. i+Q-1: the 2Q-1 steps before the one that uses it.  The stamp test covers
+// exactly those.
 // ---------------------------------------------------------------------------------------------
 constexpr int kHead = 8192;            // columns kept in LDS
-constexpr int kStamps = 32768;         // stamp table entries (16-bit step numbers)
+constexpr int kStamps = 16384;         // entries of each of the two stamp tables (16-bit step numbers)
 constexpr int kQ = 4;                  // prefetch distance of tail values, in steps
 constexpr int kRing = 2 * kQ;          // prefetch distance of row entries
 constexpr int kRowChunks = 2;          // entries of a row held in registers: 2*64
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
 {
     using TV = typename StateType<LOSS>::type;
     __shared__ TV head[kHead];
-    __shared__ uint16_t stamps[kStamps];
+    __shared__ uint16_t stamps[2][kStamps];
 
     const int lane = threadIdx.x;
     const int chain = a.order[blockIdx.x];
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
         return;
     }
     for (int c = lane; c < kHead; c += kWave) head[c] = (TV)0;
-    for (int c = lane; c < kStamps; c += kWave) stamps[c] = 0;
+    for (int c = lane; c < 2 * kStamps; c += kWave) (&stamps[0][0])[c] = 0;
     for (int64_t c = kHead + lane; c < d; c += kWave) v[c] = (TV)0;
     TV *dump = v + lane;                // per-lane scratch target for stores that must not count
                                         // (head columns of v are unused while the chain runs)
@@ -219,7 +221,10 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
         }
     };
 
-    const uint16_t kWindowSteps = 3 * kQ;
+    const uint16_t kWindowSteps = 2 * kQ;
+    // the two stamp slots of a column: columns that share the first differ in the second
+    auto slot_a = [](int32_t col) { return col & (kStamps - 1); };
+    auto slot_b = [](int32_t col) { return (int)(((uint32_t)col + ((uint32_t)col >> 14) * 2731u) & (kStamps - 1)); };
     // One step at in-window position j, absolute step number `step`.
     auto do_step = [&](int slot, int vslot, int j, int64_t step) {
         const int len = row_len(j);
@@ -238,9 +243,10 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
             is_head[c] = in && col[c] < kHead;
             is_tail[c] = in && col[c] >= kHead;
             const TV hv = head[is_head[c] ? col[c] : 0];
-            const uint16_t st = stamps[is_tail[c] ? (col[c] & (kStamps - 1)) : 0];
+            const uint16_t sa = stamps[0][is_tail[c] ? slot_a(col[c]) : 0];
+            const uint16_t sb = stamps[1][is_tail[c] ? slot_b(col[c]) : 0];
             vv[c] = is_head[c] ? hv : (is_tail[c] ? vr[vslot][c] : (TV)0);
-            stale = stale || (is_tail[c] && (uint16_t)(now - st) < kWindowSteps);
+            stale = stale || (is_tail[c] && (uint16_t)(now - sa) < kWindowSteps && (uint16_t)(now - sb) < kWindowSteps);
         }
         if (__any(stale)) {             // drain, then read this step's tail values again
 #pragma unroll
@@ -274,7 +280,10 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
         for (int c = 0; c < kRowChunks; ++c) {
             const TV nv = vv[c] + coef * (TV)val[c];
             if (is_head[c]) head[col[c]] = nv;
-            if (is_tail[c]) stamps[col[c] & (kStamps - 1)] = now;
+            if (is_tail[c]) {
+                stamps[0][slot_a(col[c])] = now;
+                stamps[1][slot_b(col[c])] = now;
+            }
             *(is_tail[c] ? v + col[c] : dump) = nv;       // one store per chunk, whatever the data
         }
         for (int e0 = kRowChunks * kWave; e0 < len; e0 += kWave) {
@@ -288,7 +297,10 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
             } else {
                 const TV cur = hidden_load(in ? v + xc : dump);
                 hidden_store(in ? v + xc : dump, in ? cur + coef * (TV)xv : cur);
-                if (in) stamps[xc & (kStamps - 1)] = now;
+                if (in) {
+                    stamps[0][slot_a(xc)] = now;
+                    stamps[1][slot_b(xc)] = now;
+                }
             }
         }
     };
@@ -344,6 +356,7 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
 
 hipError_t launch_csr(const Plan &p, const ChainArgs &a, hipStream_t s)
 {
+    if (p.prefetch == 8) return launch_csr_pair(p, a, s);
     if (p.prefetch > 1) {       // the cached kernel (its lazy scale is never folded: see the planner)
         if (p.loss == WPSGD_HINGE)
             hipLaunchKernelGGL((chain_csr_cached_kernel<kLossHinge>), dim3(a.k), dim3(kWave), 0, s, a);

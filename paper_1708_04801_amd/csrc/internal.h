@@ -53,6 +53,7 @@ struct Plan {
 hipError_t launch_dense_reg(const Plan &p, const ChainArgs &a, hipStream_t s);
 hipError_t launch_dense_mem(const Plan &p, const ChainArgs &a, hipStream_t s);
 hipError_t launch_csr(const Plan &p, const ChainArgs &a, hipStream_t s);
+hipError_t launch_csr_pair(const Plan &p, const ChainArgs &a, hipStream_t s);   // two waves per chain
 bool dense_reg_has(const Plan &p);   // is (dtype, loss, threads, ept, vec, B, P) instantiated?
 
 hipError_t launch_combine(const float *W, const double *a_dev, int k, int64_t d, float *w_out,

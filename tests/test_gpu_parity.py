@@ -256,23 +256,33 @@ def test_many_more_chains_than_compute_units():
 
 # ------------------------------------------------------------------ CSR chains
 
-@pytest.mark.parametrize("plan", [None, {"prefetch": 1}])
+# The three sparse kernels: two waves per chain (the default), one wave with head columns in LDS, plain.
+SPARSE_PLANS = [None, {"prefetch": 4}, {"prefetch": 1}]
+SPARSE_TAGS = {None: "P=8", 4: "P=4", 1: "P=1"}
+CACHED_PLANS = [None, {"prefetch": 4}]
+
+
+def _sparse_tag(plan):
+    return SPARSE_TAGS[plan["prefetch"] if plan else None]
+
+
+@pytest.mark.parametrize("plan", SPARSE_PLANS)
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
 def test_sparse_chains_small(loss, plan):
-    """plan None: head columns in LDS, tail values prefetched; prefetch 1: the plain kernel."""
     w = wl.sparse_hinge(m=5000, d=1 << 14, k=12, n_median=300)
     w.loss = loss
     w.n_steps[3] = 0
     w.n_steps[5] = 1
     X = api.matrix_from_workload(w)
     desc = api.wpsgd_describe_plan(X, w.k, loss, plan)
-    assert ("P=4" in desc) == (plan is None)
+    assert _sparse_tag(plan) in desc
     W = gpu_chains(w, plan=plan, X=X)
     check_against_oracle(w, W, label=f"sparse small [{desc}]")
     assert torch.equal(W, gpu_chains(w, plan=plan, X=X))
 
 
-def test_sparse_tail_conflicts_are_caught():
+@pytest.mark.parametrize("plan", CACHED_PLANS)
+def test_sparse_tail_conflicts_are_caught(plan):
     """Few tail columns and many steps: consecutive steps keep writing the columns the next
     ones have already fetched, so the stale-value check has to fire all the time."""
     rng = np.random.default_rng(45)
@@ -292,7 +302,40 @@ def test_sparse_tail_conflicts_are_caught():
         w = wl.Workload("tail_conflicts", loss, 0.3, 1e-4, 9, np.array([900, 257, 64, 3], dtype=np.int64), y, m, d,
                         row_ptr=np.array(rp, dtype=np.int64), col_idx=np.array(ci, dtype=np.int32),
                         vals=np.array(va, dtype=np.float32))
-        check_against_oracle(w, gpu_chains(w), label="tail conflicts")
+        check_against_oracle(w, gpu_chains(w, plan=plan), label=f"tail conflicts {plan}")
+
+
+@pytest.mark.parametrize("plan", CACHED_PLANS)
+@pytest.mark.parametrize("period", [1, 3, 7, 8, 9, 12, 16])
+def test_sparse_tail_conflicts_at_a_fixed_distance(period, plan):
+    """Tail columns that come back exactly every `period` steps: model values fetched ahead of
+    time are stale for short periods (the stale-value check must fire) and must be fresh for
+    long ones (the check does not fire, the early fetch must already see the last write)."""
+    m, n_steps, seed = 4096, 700, 17
+    visits = api.wpsgd_sample_indices(seed, 0, 0, n_steps, m)
+    first = {}
+    for t, r in enumerate(visits.tolist()):
+        first.setdefault(r, t)
+    rng = np.random.default_rng(period)
+    d = 8192 + 3 * period + 8
+    rp, ci, va = [0], [], []
+    for r in range(m):
+        cols = np.sort(rng.choice(8192, size=10, replace=False)).tolist()
+        if r in first:
+            cols += [8192 + 3 * (first[r] % period) + q for q in range(3)]
+        v = rng.standard_normal(len(cols))
+        v /= np.linalg.norm(v)
+        ci += cols
+        va += v.tolist()
+        rp.append(len(ci))
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    for loss in (wl.HINGE, wl.LOGISTIC):
+        w = wl.Workload("tail_period", loss, 0.4, 1e-4, seed, np.array([n_steps], dtype=np.int64), y, m, d,
+                        row_ptr=np.array(rp, dtype=np.int64), col_idx=np.array(ci, dtype=np.int32),
+                        vals=np.array(va, dtype=np.float32))
+        X = api.matrix_from_workload(w)
+        assert _sparse_tag(plan) in api.wpsgd_describe_plan(X, 1, loss, plan)
+        check_against_oracle(w, gpu_chains(w, X=X, plan=plan), label=f"tail period {period} {plan}")
 
 
 def test_sparse_heavy_shrink_takes_the_plain_kernel():
@@ -302,7 +345,8 @@ def test_sparse_heavy_shrink_takes_the_plain_kernel():
     check_against_oracle(w, gpu_chains(w, X=X), label="sparse heavy shrink")
 
 
-def test_sparse_rows_longer_than_the_register_window():
+@pytest.mark.parametrize("plan", SPARSE_PLANS)
+def test_sparse_rows_longer_than_the_register_window(plan):
     rng = np.random.default_rng(44)
     m, d = 40, 20000
     rp, ci, va = [0], [], []
@@ -318,7 +362,9 @@ def test_sparse_rows_longer_than_the_register_window():
     w = wl.Workload("long_rows", wl.HINGE, 0.3, 1e-2, 9, np.array([150, 80, 0], dtype=np.int64), y, m, d,
                     row_ptr=np.array(rp, dtype=np.int64), col_idx=np.array(ci, dtype=np.int32),
                     vals=np.array(va, dtype=np.float32))
-    check_against_oracle(w, gpu_chains(w), label="long sparse rows")
+    for loss in (wl.HINGE, wl.LOGISTIC):
+        w.loss = loss
+        check_against_oracle(w, gpu_chains(w, plan=plan), label=f"long sparse rows {plan}")
 
 
 # ------------------------------------------------------------------ error paths
