@@ -343,6 +343,18 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
             for (int u = 0; u < kG; ++u) {
                 const int64_t t = g * kG + u;
                 const char *hdr_t = ring0 + off_cur + u * kStepBytes + kRecordBytes;      // scalars of step t
+                // Model values and stamps of step t first: they queue right behind the previous
+                // step's LDS writes and everything below waits for them.
+                const uint16_t now = (uint16_t)t;
+                TV hv[kChunks];
+                uint16_t sa[kChunks], sb[kChunks];
+#pragma unroll
+                for (int c = 0; c < kChunks; ++c) {
+                    const pu32x4 r = rec[u][c];
+                    hv[c] = *reinterpret_cast<const TV *>(lds + r[1]);
+                    sa[c] = *reinterpret_cast<const uint16_t *>(lds + L::stamp_a + (r[3] & 0xffffu));
+                    sb[c] = *reinterpret_cast<const uint16_t *>(lds + L::stamp_b + ((r[3] >> 16) & 0x7fffu));
+                }
                 {   // records and scalars of step t+kTQ+1
                     const int uu = u + kTQ + 1;
                     const uint32_t src = (uu < kG ? off_cur : off_nxt) + (uu % kG) * kStepBytes;
@@ -355,7 +367,6 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                 if (t < n) {
                     const StepScalars<TV> sc = scr[u];
                     const int len = __builtin_amdgcn_readfirstlane(lenr[u]);
-                    const uint16_t now = (uint16_t)t;
                     TV vv[kChunks];
                     float val[kChunks];
                     bool tail[kChunks];
@@ -364,13 +375,10 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                     for (int c = 0; c < kChunks; ++c) {
                         const pu32x4 r = rec[u][c];
                         val[c] = __uint_as_float(r[0]);
-                        const TV hv = *reinterpret_cast<const TV *>(lds + r[1]);
-                        const uint16_t sa = *reinterpret_cast<const uint16_t *>(lds + L::stamp_a + (r[3] & 0xffffu));
-                        const uint16_t sb = *reinterpret_cast<const uint16_t *>(lds + L::stamp_b + ((r[3] >> 16) & 0x7fffu));
                         tail[c] = (int32_t)r[3] < 0;
-                        // evaluated for every lane (no short circuit: the stamp reads must not sit under a branch)
-                        stale |= tail[c] & ((uint16_t)(now - sa) < kRecent) & ((uint16_t)(now - sb) < kRecent);
-                        vv[c] = tail[c] ? vr[u][c] : hv;
+                        // evaluated for every lane (no short circuit: nothing here sits under a branch)
+                        stale |= tail[c] & ((uint16_t)(now - sa[c]) < kRecent) & ((uint16_t)(now - sb[c]) < kRecent);
+                        vv[c] = tail[c] ? vr[u][c] : hv[c];
                     }
                     if (__any(stale)) {             // drain, then read this step's HBM-resident values again
 #pragma unroll
