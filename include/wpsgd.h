@@ -121,6 +121,20 @@ size_t wpsgd_combine_workspace(int k, int64_t d);
 int wpsgd_combine(const float *W, const double *a, int k, int64_t d, float *w_out,
                   void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- objective and prediction error of a model (Eq. 3 with the loss of Eq. 4) ----
+ *   out[0] = lambda/2 * |w|^2 + (1/m) * sum_j L(x_j, y_j, w.x_j)
+ *   out[1] = fraction of rows with y_j * (w.x_j) <= 0     (the error rate the experiments report)
+ * Dot products, losses and sums are carried in fp64; the result does not depend on timing.
+ *   X, y     DEVICE, as for wpsgd_run_chains (to evaluate on part of a data set, pass a matrix
+ *            that describes those rows: an offset `dense` or `row_ptr` pointer and their count)
+ *   w        DEVICE, d entries fp32 (for instance the output of wpsgd_combine)
+ *   out      DEVICE, two doubles, 8-byte aligned
+ *   workspace DEVICE scratch of at least wpsgd_objective_workspace(X) bytes, 256-byte aligned
+ * Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, UNSUPPORTED (d >= 2^29), HIP_ERROR.                    */
+size_t wpsgd_objective_workspace(const wpsgd_matrix *X);
+int wpsgd_objective(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
+                    double *out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- sample stream (stands for the per-node shuffle and n-th-example fetch of Algorithm 1) ----
  * Row visited by chain `chain` at step n (0-based):
  *   (r0,..) = Philox4x32-10(counter = (n mod 2^32, n div 2^32, chain, 0),

@@ -25,7 +25,7 @@ EXPORTS = [
     "wpsgd_run_chains_workspace", "wpsgd_run_chains", "wpsgd_weights", "wpsgd_weights_rate",
     "wpsgd_benefit_margin", "wpsgd_combine_workspace", "wpsgd_combine", "wpsgd_sample_indices",
     "wpsgd_sample_indices_device", "wpsgd_strerror", "wpsgd_last_hip_error", "wpsgd_describe_plan",
-    "wpsgd_stream_rows",
+    "wpsgd_stream_rows", "wpsgd_objective_workspace", "wpsgd_objective",
 ]
 
 
@@ -80,6 +80,9 @@ def load():
     L.wpsgd_last_hip_error.argtypes = []
     L.wpsgd_describe_plan.argtypes = [pm, ci, ci, pp, ctypes.c_char_p, sz]
     L.wpsgd_stream_rows.argtypes = [pm, ci, i64, u64, vp, vp]
+    L.wpsgd_objective_workspace.argtypes = [pm]
+    L.wpsgd_objective_workspace.restype = sz
+    L.wpsgd_objective.argtypes = [pm, vp, vp, f64, ci, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -238,6 +241,28 @@ def wpsgd_combine(W: torch.Tensor, a, w_out: Optional[torch.Tensor] = None,
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_combine")
     return w_out
+
+
+def wpsgd_objective_workspace(X: Matrix) -> int:
+    cm = X.c_struct()
+    return int(load().wpsgd_objective_workspace(ctypes.byref(cm)))
+
+
+def wpsgd_objective(X: Matrix, y: torch.Tensor, w: torch.Tensor, lam, loss, out: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Returns a 2-element float64 GPU tensor: [regularised objective, error rate] of model w on (X, y)."""
+    assert y.is_cuda and y.dtype == torch.float32 and y.numel() == X.m
+    assert w.is_cuda and w.dtype == torch.float32 and w.numel() == X.d and w.is_contiguous()
+    cm = X.c_struct()
+    if out is None:
+        out = torch.empty(2, dtype=torch.float64, device=y.device)
+    if workspace is None:
+        workspace = _workspace(wpsgd_objective_workspace(X), y.device)
+    rc = load().wpsgd_objective(ctypes.byref(cm), y.data_ptr(), w.data_ptr(), float(lam), int(loss), out.data_ptr(),
+                                workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_objective")
+    return out
 
 
 def wpsgd_sample_indices(seed, chain, n0, count, m) -> np.ndarray:

@@ -32,6 +32,7 @@ FLAGS = [
 UNITS = [
     ("api", "api.hip", []),
     ("combine", "combine.hip", []),
+    ("objective", "objective.hip", []),
     ("chain_dense_mem", "chain_dense_mem.hip", []),
     ("chain_csr", "chain_csr.hip", []),
     ("chain_csr_pair", "chain_csr_pair.hip", []),

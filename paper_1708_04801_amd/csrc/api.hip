@@ -404,6 +404,39 @@ int wpsgd_combine(const float *W, const double *a, int k, int64_t d, float *w_ou
     return e == hipSuccess ? WPSGD_OK : hip_fail(e);
 }
 
+size_t wpsgd_objective_workspace(const wpsgd_matrix *X)
+{
+    if (check_matrix(X) != WPSGD_OK) return 0;
+    return align256(objective_partials_bytes(X->m));
+}
+
+int wpsgd_objective(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
+                    double *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_matrix(X);
+    if (rc != WPSGD_OK) return rc;
+    if (!y || !w || !out || !(lambda >= 0.0)) return WPSGD_INVALID_ARG;
+    if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
+    if ((uintptr_t)out % sizeof(double) != 0) return WPSGD_INVALID_ARG;
+    if (X->d >= (1ll << 29)) return WPSGD_UNSUPPORTED;           // 32-bit byte offsets into a row and into w
+    if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
+    if (workspace_bytes < wpsgd_objective_workspace(X)) return WPSGD_WORKSPACE_TOO_SMALL;
+    ChainArgs a{};
+    a.dense = X->dense;
+    a.ld = X->ld;
+    a.row_ptr = X->row_ptr;
+    a.col_idx = X->col_idx;
+    a.vals = X->vals;
+    a.y = y;
+    a.m = X->m;
+    a.d = X->d;
+    int vec = 1;
+    if (X->dense && (uintptr_t)w % 16 == 0) vec = dense_vec(X);
+    hipError_t e = launch_objective(a, X->dense ? (int)X->dtype : WPSGD_F32, vec, (int)loss, w, lambda,
+                                    static_cast<double *>(workspace), out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
 int wpsgd_sample_indices(uint64_t seed, int chain, int64_t n0, int64_t count, int64_t m,
                          int64_t *out_host)
 {

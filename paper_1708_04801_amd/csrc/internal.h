@@ -61,6 +61,11 @@ hipError_t launch_combine(const float *W, const double *a_dev, int k, int64_t d,
 hipError_t launch_stream_rows(const void *X, int64_t row_stride, uint32_t row_bytes, uint32_t m,
                               int groups, int64_t rows_per_group, uint32_t seed_lo, uint32_t seed_hi,
                               float *sink, hipStream_t s);
+// Objective / error-rate evaluator: ChainArgs carries the matrix, the labels and m, d only.
+int64_t objective_grid(int64_t m);
+size_t objective_partials_bytes(int64_t m);
+hipError_t launch_objective(const ChainArgs &a, int dtype, int vec, int loss, const float *w, double lambda,
+                            double *partials, double *out, hipStream_t s);
 hipError_t launch_sample_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, int64_t n0,
                               int64_t count, uint32_t m, int64_t *out, hipStream_t s);
 

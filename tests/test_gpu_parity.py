@@ -367,6 +367,64 @@ def test_sparse_rows_longer_than_the_register_window(plan):
         check_against_oracle(w, gpu_chains(w, plan=plan), label=f"long sparse rows {plan}")
 
 
+# ------------------------------------------------------------------ objective and error rate
+
+def _check_objective(w, wvec, lam, label):
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    got = api.wpsgd_objective(X, y, torch.from_numpy(wvec).cuda(), lam, w.loss).cpu().numpy()
+    Xo = orc.CSR(w.row_ptr, w.col_idx, w.vals, w.d) if w.is_csr else orc.Dense(w.dense)
+    obj, err = orc.objective(Xo, w.y, wvec.astype(np.float64), lam, w.loss)
+    assert got[0] == pytest.approx(obj, rel=1e-11, abs=1e-13), label
+    assert abs(got[1] - err) <= 1.0 / w.m, label          # a row with y*yhat within rounding of 0 may flip
+
+
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+@pytest.mark.parametrize("d", [1, 63, 64, 300, 512, 1000, 4096, 5000])
+def test_objective_dense(d, loss):
+    rng = np.random.default_rng(100 + d)
+    m = 777
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    wvec = rng.standard_normal(d).astype(np.float32) * 2
+    y = np.where(X @ wvec + 0.5 * rng.standard_normal(m) >= 0, 1.0, -1.0).astype(np.float32)
+    w = wl.Workload("obj", loss, 0.1, 1e-3, 0, np.array([1], dtype=np.int64), y, m, d, dense=X)
+    _check_objective(w, wvec, 0.02, f"dense d={d}")
+    _check_objective(w, np.zeros(d, dtype=np.float32), 0.5, f"dense d={d} w=0")     # log 2 or 1, every row wrong
+    w16 = wl.Workload("obj16", loss, 0.1, 1e-3, 0, np.array([1], dtype=np.int64), y, m, d, dense=wl.f32_to_bf16_bits(X))
+    _check_objective(w16, wvec, 0.02, f"bf16 d={d}")
+
+
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_objective_sparse_and_row_subsets(loss):
+    w = wl.sparse_hinge(m=6000, d=1 << 15, k=2, n_median=10)
+    w.loss = loss
+    rng = np.random.default_rng(5)
+    wvec = (rng.standard_normal(w.d) * (rng.random(w.d) < 0.3)).astype(np.float32)
+    _check_objective(w, wvec, 1e-3, "sparse")
+    # the last 1000 rows only, as a held-out set: the same arrays behind an offset row pointer
+    X = api.matrix_from_workload(w)
+    held = api.Matrix(1000, w.d, row_ptr=X.row_ptr[5000:], col_idx=X.col_idx, vals=X.vals)
+    y = torch.from_numpy(w.y).cuda()
+    got = api.wpsgd_objective(held, y[5000:], torch.from_numpy(wvec).cuda(), 1e-3, loss).cpu().numpy()
+    rp = w.row_ptr[5000:] - w.row_ptr[5000]
+    lo, hi = w.row_ptr[5000], w.row_ptr[6000]
+    obj, err = orc.objective(orc.CSR(rp, w.col_idx[lo:hi], w.vals[lo:hi], w.d), w.y[5000:], wvec.astype(np.float64), 1e-3, loss)
+    assert got[0] == pytest.approx(obj, rel=1e-11)
+    assert abs(got[1] - err) <= 1e-3
+
+
+def test_objective_rejects_bad_arguments():
+    X = api.Matrix(4, 8, dense=torch.zeros((4, 8), dtype=torch.float32, device="cuda"))
+    y = torch.ones(4, dtype=torch.float32, device="cuda")
+    w = torch.zeros(8, dtype=torch.float32, device="cuda")
+    with pytest.raises(api.WpsgdError) as e:
+        api.wpsgd_objective(X, y, w, -1.0, wl.HINGE)
+    assert e.value.status == api.INVALID_ARG
+    with pytest.raises(api.WpsgdError) as e:
+        api.wpsgd_objective(X, y, w, 0.1, wl.HINGE, workspace=torch.empty(256, dtype=torch.uint8, device="cuda")[:16])
+    assert e.value.status in (api.INVALID_ARG, api.WORKSPACE_TOO_SMALL)
+
+
 # ------------------------------------------------------------------ error paths
 
 def test_run_chains_rejects_bad_arguments():
