@@ -77,7 +77,7 @@ typedef struct wpsgd_plan {
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----
  *
- * Chain i (i = 0..k-1) starts from w = 0 and performs n_steps[i] updates
+ * Chain i (i = 0..k-1) starts from w = 0 (Algorithm 1) and performs n_steps[i] updates
  *     w <- (1 - eta*lambda) * w  -  eta * dL/dyhat(y_j, w.x_j) * x_j
  * where j is the row its own sample stream names at that step (see
  * wpsgd_sample_indices).  The result of chain i is written to W[i*d .. i*d+d).
@@ -99,6 +99,17 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
                      double eta, double lambda, wpsgd_loss loss, uint64_t seed,
                      float *W, void *workspace, size_t workspace_bytes,
                      const wpsgd_plan *plan, void *stream);
+
+/* The same from a common start vector and from inside the sample streams: chain i starts from
+ * w_start (DEVICE, d entries fp32; NULL means zero) and takes the rows its stream names at steps
+ * step_offsets[i] .. step_offsets[i] + n_steps[i] - 1 (HOST, k entries >= 0; NULL means zero).
+ * With both NULL this is wpsgd_run_chains.  The experiments of the paper start every node from a
+ * constant vector; restarting all chains from the weighted average every so many steps, each chain
+ * continuing its own stream, is the periodic averaging of Section III (Deduction 2).            */
+int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
+                          double eta, double lambda, wpsgd_loss loss, uint64_t seed,
+                          const float *w_start, const int64_t *step_offsets, float *W,
+                          void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream);
 
 /* ---- weights (Eq. 6; Eq. 8 for a chosen contraction rate r) ----
  *   a[i] = rate^{T_i} / sum_j rate^{T_j},  T_i = max_j n_steps[j] - n_steps[i],

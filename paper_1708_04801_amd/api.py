@@ -26,6 +26,7 @@ EXPORTS = [
     "wpsgd_benefit_margin", "wpsgd_combine_workspace", "wpsgd_combine", "wpsgd_sample_indices",
     "wpsgd_sample_indices_device", "wpsgd_strerror", "wpsgd_last_hip_error", "wpsgd_describe_plan",
     "wpsgd_stream_rows", "wpsgd_objective_workspace", "wpsgd_objective",
+    "wpsgd_run_chains_from",
 ]
 
 
@@ -67,6 +68,7 @@ def load():
     L.wpsgd_run_chains_workspace.argtypes = [pm, ci, ci, pp]
     L.wpsgd_run_chains_workspace.restype = sz
     L.wpsgd_run_chains.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, sz, pp, vp]
+    L.wpsgd_run_chains_from.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, vp, vp, sz, pp, vp]
     L.wpsgd_weights.argtypes = [ci, vp, f64, f64, vp]
     L.wpsgd_weights_rate.argtypes = [ci, vp, f64, vp]
     L.wpsgd_benefit_margin.argtypes = [ci, vp, f64, vp]
@@ -190,6 +192,40 @@ def wpsgd_run_chains(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
                                  workspace.data_ptr(), workspace.numel(), pl, _stream(stream))
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_run_chains")
+    return W
+
+
+def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
+                          w_start: Optional[torch.Tensor] = None, step_offsets=None,
+                          W: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                          plan=None, stream=None) -> torch.Tensor:
+    """wpsgd_run_chains from a common start vector (d float32 on the GPU, or None for zero) and
+    from per-chain positions in the sample streams (k integers, or None for zero)."""
+    n = _steps(n_steps)
+    k = int(n.size)
+    dev = y.device
+    assert y.is_cuda and y.dtype == torch.float32 and y.numel() == X.m
+    if w_start is not None:
+        assert w_start.is_cuda and w_start.dtype == torch.float32 and w_start.is_contiguous() and w_start.numel() == X.d
+    off = None
+    if step_offsets is not None:
+        off = _steps(step_offsets)
+        assert off.size == k
+    if W is None:
+        W = torch.empty((k, X.d), dtype=torch.float32, device=dev)
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.shape == (k, X.d)
+    cm = X.c_struct()
+    pl = _plan(plan)
+    if workspace is None:
+        need = load().wpsgd_run_chains_workspace(ctypes.byref(cm), k, int(loss), pl)
+        workspace = _workspace(need, dev)
+    rc = load().wpsgd_run_chains_from(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, float(eta),
+                                      float(lam), int(loss), int(seed),
+                                      w_start.data_ptr() if w_start is not None else None,
+                                      off.ctypes.data if off is not None else None, W.data_ptr(),
+                                      workspace.data_ptr(), workspace.numel(), pl, _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_run_chains_from")
     return W
 
 

@@ -1,6 +1,7 @@
 // The C ABI of libwpsgd (see wpsgd.h): argument checks, the kernel planner, the host-side
 // weights of Eq. 6 / Eq. 8, and the small host->device hand-overs the kernels need.
 #include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -160,9 +161,10 @@ static size_t state_elem_bytes(wpsgd_loss loss)
     return loss == WPSGD_HINGE ? sizeof(double) : sizeof(float);
 }
 
+// workspace header: chain order, then step counts and stream offsets in that order
 static size_t header_bytes(int k)
 {
-    return align256((size_t)k * sizeof(int32_t)) + align256((size_t)k * sizeof(int64_t));
+    return align256((size_t)k * sizeof(int32_t)) + 2 * align256((size_t)k * sizeof(int64_t));
 }
 
 // Host arrays (chain order, step counts, weights) reach the device through a small ring of pinned
@@ -268,11 +270,23 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
                      double eta, double lambda, wpsgd_loss loss, uint64_t seed, float *W,
                      void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream)
 {
+    return wpsgd_run_chains_from(X, y, k, n_steps, eta, lambda, loss, seed, nullptr, nullptr, W, workspace,
+                                 workspace_bytes, plan, stream);
+}
+
+int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
+                          double eta, double lambda, wpsgd_loss loss, uint64_t seed,
+                          const float *w_start, const int64_t *step_offsets, float *W,
+                          void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream)
+{
     int rc = check_matrix(X);
     if (rc != WPSGD_OK) return rc;
     if (!y || !W) return WPSGD_INVALID_ARG;
     rc = check_steps(k, n_steps);
     if (rc != WPSGD_OK) return rc;
+    if (step_offsets)
+        for (int i = 0; i < k; ++i)
+            if (step_offsets[i] < 0 || step_offsets[i] > INT64_MAX - n_steps[i]) return WPSGD_INVALID_ARG;
     if (!(eta > 0.0) || !(lambda >= 0.0) || !(eta * lambda < 1.0)) return WPSGD_INVALID_ARG;
     if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
     Plan p;
@@ -294,12 +308,18 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
     const size_t order_bytes = align256((size_t)k * sizeof(int32_t));
     std::vector<char> header(header_bytes(k), 0);
     std::memcpy(header.data(), order.data(), (size_t)k * sizeof(int32_t));
+    const size_t steps_bytes = align256((size_t)k * sizeof(int64_t));
     int64_t *sorted_steps = reinterpret_cast<int64_t *>(header.data() + order_bytes);
-    for (int b = 0; b < k; ++b) sorted_steps[b] = n_steps[order[b]];
+    int64_t *sorted_offsets = reinterpret_cast<int64_t *>(header.data() + order_bytes + steps_bytes);
+    for (int b = 0; b < k; ++b) {
+        sorted_steps[b] = n_steps[order[b]];
+        sorted_offsets[b] = step_offsets ? step_offsets[order[b]] : 0;
+    }
 
     char *ws = static_cast<char *>(workspace);
     int32_t *order_dev = reinterpret_cast<int32_t *>(ws);
     int64_t *steps_dev = reinterpret_cast<int64_t *>(ws + order_bytes);
+    int64_t *offsets_dev = reinterpret_cast<int64_t *>(ws + order_bytes + steps_bytes);
     void *state_dev = ws + header_bytes(k);
     rc = upload(ws, header.data(), header.size(), s);
     if (rc != WPSGD_OK) return rc;
@@ -316,6 +336,8 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
     a.k = k;
     a.order = order_dev;
     a.nsteps = steps_dev;
+    a.step0 = offsets_dev;
+    a.w_start = w_start;
     a.eta = eta;
     a.rho = 1.0 - eta * lambda;
     a.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);

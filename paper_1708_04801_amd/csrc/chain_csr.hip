@@ -20,8 +20,9 @@ __global__ __launch_bounds__(kWave) void chain_csr_kernel(ChainArgs a)
     const int64_t d = a.d;
     TV *v = static_cast<TV *>(a.state) + (int64_t)chain * d;
 
-    for (int64_t col = lane; col < d; col += kWave) v[col] = (TV)0;
-    __syncthreads();   // the zeros must be visible to whichever lane gathers them later
+    for (int64_t col = lane; col < d; col += kWave) v[col] = a.w_start ? (TV)a.w_start[col] : (TV)0;
+    __syncthreads();   // the start values must be visible to whichever lane gathers them later
+    const int64_t step0 = a.step0[blockIdx.x];
 
     RowWindow win;
     win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
@@ -29,7 +30,7 @@ __global__ __launch_bounds__(kWave) void chain_csr_kernel(ChainArgs a)
     const double rho = a.rho, inv_rho = 1.0 / a.rho, eta = a.eta;
 
     for (int64_t step = 0; step < n; ++step) {
-        const uint32_t row = win.get(step);
+        const uint32_t row = win.get(step0 + step);
         const int64_t lo = a.row_ptr[row], hi = a.row_ptr[(int64_t)row + 1];
         const double y = (double)a.y[row];
 
@@ -149,13 +150,23 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
     float *out = a.W + (int64_t)chain * d;
     const int64_t nnz = a.row_ptr[a.m];
 
-    if (n == 0 || nnz == 0) {           // no steps, or no entries at all: the model stays zero
-        for (int64_t c = lane; c < d; c += kWave) out[c] = 0.0f;
+    const int64_t step0 = a.step0[blockIdx.x];
+    if (nnz == 0) {                     // no entries at all: every step only shrinks the start vector
+        double s_all = 1.0, pw = a.rho;
+        for (int64_t e = n; e > 0; e >>= 1) {
+            if (e & 1) s_all *= pw;
+            pw *= pw;
+        }
+        for (int64_t c = lane; c < d; c += kWave) out[c] = a.w_start ? (float)(s_all * (double)a.w_start[c]) : 0.0f;
         return;
     }
-    for (int c = lane; c < kHead; c += kWave) head[c] = (TV)0;
+    if (n == 0) {                       // no steps: the chain returns its start vector
+        for (int64_t c = lane; c < d; c += kWave) out[c] = a.w_start ? a.w_start[c] : 0.0f;
+        return;
+    }
+    for (int c = lane; c < kHead; c += kWave) head[c] = (a.w_start && c < d) ? (TV)a.w_start[c] : (TV)0;
     for (int c = lane; c < 2 * kStamps; c += kWave) (&stamps[0][0])[c] = 0;
-    for (int64_t c = kHead + lane; c < d; c += kWave) v[c] = (TV)0;
+    for (int64_t c = kHead + lane; c < d; c += kWave) v[c] = a.w_start ? (TV)a.w_start[c] : (TV)0;
     TV *dump = v + lane;                // per-lane scratch target for stores that must not count
                                         // (head columns of v are unused while the chain runs)
     __syncthreads();
@@ -181,7 +192,7 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
     float y_b;
     TV zs_tab = (TV)0, cs_tab = (TV)0;
     auto load_window = [&](int64_t w, int64_t &lo, int &len, float &y) {
-        const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, w * kWave, m32);
+        const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32);
         const int64_t p0 = a.row_ptr[row], p1 = a.row_ptr[(int64_t)row + 1];
         lo = p0;
         len = (int)(p1 - p0);

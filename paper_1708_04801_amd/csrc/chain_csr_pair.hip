@@ -172,14 +172,25 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
     float *out = a.W + (int64_t)chain * d;
     const int64_t nnz = a.row_ptr[a.m];
 
-    if (n == 0 || nnz == 0) {           // no steps, or no entries at all: the model stays zero
-        for (int64_t c = tid; c < d; c += 2 * kWave) out[c] = 0.0f;
+    const int64_t step0 = a.step0[blockIdx.x];
+    if (nnz == 0) {                     // no entries at all: every step only shrinks the start vector
+        double s_all = 1.0, pw = a.rho;
+        for (int64_t e = n; e > 0; e >>= 1) {
+            if (e & 1) s_all *= pw;
+            pw *= pw;
+        }
+        for (int64_t c = tid; c < d; c += 2 * kWave) out[c] = a.w_start ? (float)(s_all * (double)a.w_start[c]) : 0.0f;
+        return;
+    }
+    if (n == 0) {                       // no steps: the chain returns its start vector
+        for (int64_t c = tid; c < d; c += 2 * kWave) out[c] = a.w_start ? a.w_start[c] : 0.0f;
         return;
     }
     TV *head = reinterpret_cast<TV *>(lds + L::head);
-    for (int c = tid; c < kPHead + kSlots; c += 2 * kWave) head[c] = (TV)0;          // values and scratch slots
+    for (int c = tid; c < kPHead + kSlots; c += 2 * kWave)                             // values and scratch slots
+        head[c] = (a.w_start && c < kPHead && c < d) ? (TV)a.w_start[c] : (TV)0;
     for (int c = tid; c < 2 * (kPStamps + kSlots); c += 2 * kWave) reinterpret_cast<uint16_t *>(lds + L::stamp_a)[c] = 0;
-    for (int64_t c = kPHead + tid; c < d; c += 2 * kWave) v[c] = (TV)0;
+    for (int64_t c = kPHead + tid; c < d; c += 2 * kWave) v[c] = a.w_start ? (TV)a.w_start[c] : (TV)0;
     __syncthreads();
 
     const int64_t ngroups = (n + kG - 1) / kG;       // the worker runs groups 0..ngroups-1, the scout writes 0..ngroups
@@ -206,7 +217,7 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
         int len_a, len_b;
         float y_a, y_b;
         auto load_window = [&](int64_t w, int64_t &lo, int &len, float &y) {
-            const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, w * kWave, m32);
+            const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32);
             const int64_t p0 = a.row_ptr[row], p1 = a.row_ptr[(int64_t)row + 1];
             lo = p0;
             len = (int)(p1 - p0);

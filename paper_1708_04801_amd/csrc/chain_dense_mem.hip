@@ -53,7 +53,8 @@ __global__ __launch_bounds__(NT) void chain_dense_mem_kernel(ChainArgs a)
 
     for (int64_t col = (int64_t)tid * VEC; col < d; col += (int64_t)NT * VEC)
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) v[col + j] = (TV)0;
+        for (int j = 0; j < VEC; ++j) v[col + j] = a.w_start ? (TV)a.w_start[col + j] : (TV)0;
+    const int64_t step0 = a.step0[blockIdx.x];
 
     RowWindow win;
     win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(NT) void chain_dense_mem_kernel(ChainArgs a)
     int parity = 0;
 
     for (int64_t step = 0; step < n; ++step) {
-        const uint32_t row = win.get(step);
+        const uint32_t row = win.get(step0 + step);
         const TX *xr = X + (int64_t)row * a.ld;
         const double y = (double)a.y[row];
         TV acc = (TV)0;

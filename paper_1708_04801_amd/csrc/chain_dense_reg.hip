@@ -111,7 +111,11 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 
     TV v[EPT];
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) v[e] = (TV)0;
+    for (int e = 0; e < EPT; ++e) {
+        const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
+        v[e] = (a.w_start && col < a.d) ? (TV)a.w_start[col] : (TV)0;
+    }
+    const int64_t step0 = a.step0[blockIdx.x];
 
     if (n > 0) {
         uint32_t off[Frag::kChunks];               // this lane's byte offset of each chunk
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 
         const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
         auto window_rows = [&](int64_t w) {
-            return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(w * kWave + lane), m32);
+            return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(step0 + w * kWave + lane), m32);
         };
         uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
         TV zs_tab = (TV)0, cs_tab = (TV)0;   // per lane: s_l (times log2(e) for logistic), eta/s_{l+1}
@@ -333,7 +337,11 @@ __global__ __launch_bounds__(NT) void chain_dense_wide_kernel(ChainArgs a)
 
     TV v[EPT];
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) v[e] = (TV)0;
+    for (int e = 0; e < EPT; ++e) {
+        const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
+        v[e] = (a.w_start && col < a.d) ? (TV)a.w_start[col] : (TV)0;
+    }
+    const int64_t step0 = a.step0[blockIdx.x];
 
     if (n > 0) {
         const uint32_t off0 = (uint32_t)((tid * VEC) * sizeof(TX));          // chunk c adds c*NT*VEC elements
@@ -386,7 +394,7 @@ __global__ __launch_bounds__(NT) void chain_dense_wide_kernel(ChainArgs a)
                         eos_w = a.eta;
                     }
                 }
-                rows = sample_window(a.seed_lo, a.seed_hi, (uint32_t)chain, step, (uint32_t)a.m);
+                rows = sample_window(a.seed_lo, a.seed_hi, (uint32_t)chain, step0 + step, (uint32_t)a.m);
                 const double sl = s_w * rho_pow, el = eos_w * inv_rho_pow1;
                 if constexpr (LOSS == kLossHinge) {
                     zs_tab = sl;
@@ -468,7 +476,11 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
 
     TV v[EPT];
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) v[e] = (TV)0;
+    for (int e = 0; e < EPT; ++e) {
+        const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
+        v[e] = (a.w_start && col < a.d) ? (TV)a.w_start[col] : (TV)0;
+    }
+    const int64_t step0 = a.step0[blockIdx.x];
 
     if (n > 0) {
         const uint32_t off0 = (uint32_t)(tid * 16);                           // chunk c adds c*NT*16 bytes
@@ -487,7 +499,7 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
         double s_w = 1.0, eos_w = a.eta;
         const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
         auto window_rows = [&](int64_t w) {
-            return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(w * kWave + lane), m32);
+            return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(step0 + w * kWave + lane), m32);
         };
         uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
         TV zs_tab = (TV)0, cs_tab = (TV)0;     // per lane, label folded in: y*s_l (*log2 e), y*eta/s_{l+1}

@@ -25,6 +25,8 @@ struct ChainArgs {
     int k;
     const int32_t *order;     // DEVICE, k entries: chain id run by workgroup b
     const int64_t *nsteps;    // DEVICE, k entries: steps of that chain
+    const int64_t *step0;     // DEVICE, k entries: position in that chain's sample stream of its first step
+    const float *w_start;     // DEVICE, d entries: every chain starts from this vector; NULL: from zero
     // hyper-parameters (fp64 on purpose: (1-eta*lambda)^n must not be compounded in fp32)
     double eta, rho;          // rho = 1 - eta*lambda
     uint32_t seed_lo, seed_hi;

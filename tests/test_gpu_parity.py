@@ -367,6 +367,103 @@ def test_sparse_rows_longer_than_the_register_window(plan):
         check_against_oracle(w, gpu_chains(w, plan=plan), label=f"long sparse rows {plan}")
 
 
+# ------------------------------------------------------------------ start vector and stream offsets
+
+def _oracle_from(w, w_start, offsets):
+    """Every chain by the oracle's single-chain routine on an explicit index stream."""
+    Xo = orc.CSR(w.row_ptr, w.col_idx, w.vals, w.d) if w.is_csr else orc.Dense(w.dense)
+    W = np.zeros((w.k, w.d))
+    closest = np.inf
+    for i in range(w.k):
+        idx = orc.sample_indices(w.seed, i, int(offsets[i]), int(w.n_steps[i]), w.m)
+        W[i], mm = orc.sgd(Xo, w.y, idx, w.eta, w.lam, w.loss, w0=w_start.astype(np.float64))
+        closest = min(closest, mm)
+    return W, closest
+
+
+def _check_from(w, plan, label):
+    rng = np.random.default_rng(w.d + w.k)
+    w_start = (rng.standard_normal(w.d) * 0.5).astype(np.float32)
+    offsets = rng.integers(0, 500, size=w.k).astype(np.int64)
+    offsets[0] = 0
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    W = api.wpsgd_run_chains_from(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed,
+                                  w_start=torch.from_numpy(w_start).cuda(), step_offsets=offsets, plan=plan)
+    Wo, closest = _oracle_from(w, w_start, offsets)
+    if w.loss == wl.HINGE:
+        assert closest > KINK, f"{label}: a hinge step sits on the kink ({closest:.3e})"
+    Wg = W.cpu().numpy().astype(np.float64)
+    for i in range(w.k):
+        err = np.linalg.norm(Wg[i] - Wo[i]) / max(np.linalg.norm(Wo[i]), 1e-300)
+        assert err <= TOL, f"{label}: chain {i} rel L2 {err:.3e}"
+    # the defaults reproduce wpsgd_run_chains bit for bit
+    assert torch.equal(api.wpsgd_run_chains_from(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed, plan=plan),
+                       api.wpsgd_run_chains(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed, plan=plan))
+
+
+@pytest.mark.parametrize("d,plan", [(64, None), (300, None), (4096, None), (4096, {"block_steps": 4}),
+                                    (5000, {"state_in_hbm": 1}), (20000, None), (20000, {"rows": 3})])
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_dense_chains_from_a_start_vector_and_stream_offsets(d, plan, loss):
+    rng = np.random.default_rng(d + 3 * loss)
+    m = 300
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = np.array([130, 0, 64, 7], dtype=np.int64)
+    w = wl.Workload("from_dense", loss, 0.3, 1e-2, 21, n, y, m, d, dense=X)
+    _check_from(w, plan, f"dense d={d} {plan}")
+
+
+@pytest.mark.parametrize("plan", SPARSE_PLANS)
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_sparse_chains_from_a_start_vector_and_stream_offsets(loss, plan):
+    w = wl.sparse_hinge(m=3000, d=1 << 14, k=5, n_median=150)
+    w.loss = loss
+    w.n_steps[1] = 0
+    _check_from(w, plan, f"sparse {plan}")
+
+
+def test_bf16_chains_from_a_start_vector():
+    rng = np.random.default_rng(8)
+    m, d = 64, 65536
+    bits = wl.f32_to_bf16_bits((rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32))
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    w = wl.Workload("from_bf16", wl.LOGISTIC, 0.5, 1e-3, 5, np.array([70, 3], dtype=np.int64), y, m, d, dense=bits)
+    _check_from(w, None, "bf16 widest")
+
+
+def test_periodic_averaging_restarts_chains_from_the_weighted_average():
+    """Two spans of unequal chains with a weighted average in between (Section III, Deduction 2),
+    each chain continuing its own sample stream: device path against the oracle."""
+    w = wl.tiny_hinge()
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    n1, n2 = w.n_steps // 2, w.n_steps - w.n_steps // 2
+    W1 = api.wpsgd_run_chains(X, y, n1, w.eta, w.lam, w.loss, w.seed)
+    v1 = api.wpsgd_combine(W1, api.wpsgd_weights(n1, w.eta, w.lam))
+    W2 = api.wpsgd_run_chains_from(X, y, n2, w.eta, w.lam, w.loss, w.seed, w_start=v1, step_offsets=n1)
+    v2 = api.wpsgd_combine(W2, api.wpsgd_weights(n2, w.eta, w.lam)).cpu().numpy()
+    Xo = orc.Dense(w.dense)
+    Wo1, _ = orc.run_chains(Xo, w.y, n1, w.eta, w.lam, w.loss, w.seed)
+    vo1 = orc.combine(Wo1, orc.weights(n1, w.eta, w.lam))
+    Wo2 = np.zeros_like(Wo1)
+    for i in range(w.k):
+        idx = orc.sample_indices(w.seed, i, int(n1[i]), int(n2[i]), w.m)
+        Wo2[i], _ = orc.sgd(Xo, w.y, idx, w.eta, w.lam, w.loss, w0=vo1)
+    vo2 = orc.combine(Wo2, orc.weights(n2, w.eta, w.lam))
+    assert np.linalg.norm(v2 - vo2) / np.linalg.norm(vo2) <= TOL
+
+
+def test_run_chains_from_rejects_negative_offsets():
+    w = wl.tiny_hinge()
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    with pytest.raises(api.WpsgdError) as e:
+        api.wpsgd_run_chains_from(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed, step_offsets=[0, -1, 0, 0])
+    assert e.value.status == api.INVALID_ARG
+
+
 # ------------------------------------------------------------------ objective and error rate
 
 def _check_objective(w, wvec, lam, label):

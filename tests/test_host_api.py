@@ -115,8 +115,8 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
 
 
 def test_workspace_sizes():
-    # chain order + step counts (256-byte slots) + room for the model vectors in HBM
-    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 512 + 4 * 64 * 8
+    # chain order + step counts + stream offsets (256-byte slots) + room for the model vectors in HBM
+    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 768 + 4 * 64 * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.HINGE)
     assert ws >= 128 * (1 << 20) * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.LOGISTIC)

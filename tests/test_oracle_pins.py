@@ -53,6 +53,12 @@ def test_index_range_and_uniformity():
     assert big.max() < (1 << 32) - 1 and big.max() > (1 << 31)
 
 
+def test_index_stream_from_an_offset_is_a_slice_of_the_stream():
+    whole = orc.sample_indices(9, 3, 0, 300, 1000)
+    for n0 in (0, 1, 63, 64, 65, 250):
+        assert np.array_equal(orc.sample_indices(9, 3, n0, 40, 1000), whole[n0:n0 + 40])
+
+
 def test_index_streams_differ_by_chain_step_and_seed():
     a = orc.sample_indices(0, 0, 0, 64, 1 << 20)
     assert not np.array_equal(a, orc.sample_indices(0, 1, 0, 64, 1 << 20))
