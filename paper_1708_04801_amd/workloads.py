@@ -224,6 +224,40 @@ def sparse_hinge(m=1_000_000, d=1 << 20, k=128, nnz_mean=80, n_median=10000, n_s
                     row_ptr=row_ptr, col_idx=col_idx, vals=vals)
 
 
+def analog_binary(m_train=460_000, m_test=40_000, d=100_000, n_fast=100_000, fast=8, slow=2, slow_share=0.2,
+                  data_seed=1006) -> Workload:
+    """The fully specified synthetic data of the paper's "Analog data" experiment (section V):
+    rows with 5 to 10 binary features at random positions, scaled to unit length; the label is
+    the sign of sum_i x_i * (i % 4) * (-1)^i over the 1-based feature index i (+1 where the paper
+    writes label 1, -1 where it writes 0).  The first m_train rows are for training, the rest
+    for testing.  `fast` chains run n_fast steps, `slow` chains slow_share of that (the paper's
+    unbalanced cluster: eight nodes with five times the data of the other two).  eta, lambda as
+    in the paper; meta carries its start value 4 and its fitted contraction rate 0.99999."""
+    m = m_train + m_test
+    rng = np.random.default_rng(data_seed)
+    lens = rng.integers(5, 11, size=m)
+    row_ptr = np.concatenate(([0], np.cumsum(lens))).astype(np.int64)
+    # ten distinct positions per row (rejection on the rare repeats), the first lens[r] are kept
+    cand = rng.integers(0, d, size=(m, 10))
+    while True:
+        srt = np.sort(cand, axis=1)
+        bad = (srt[:, 1:] == srt[:, :-1]).any(axis=1)
+        if not bad.any():
+            break
+        cand[bad] = rng.integers(0, d, size=(int(bad.sum()), 10))
+    keep = np.arange(10)[None, :] < lens[:, None]
+    cols = np.where(keep, cand, d)                     # dropped slots sort to the end
+    cols.sort(axis=1)
+    col_idx = cols[cols < d].astype(np.int32)           # row-major: ascending inside every row
+    i1 = col_idx.astype(np.int64) + 1                  # the paper counts features from 1
+    score = np.add.reduceat((i1 % 4) * np.where(i1 % 2 == 0, 1.0, -1.0), row_ptr[:-1])
+    vals = np.repeat(1.0 / np.sqrt(lens), lens).astype(np.float32)
+    y = np.where(score > 0, 1.0, -1.0).astype(np.float32)
+    n = np.array([n_fast] * fast + [int(round(n_fast * slow_share))] * slow, dtype=np.int64)
+    return Workload("analog_binary", HINGE, 1e-4, 0.01, 0, n, y, m, d, row_ptr=row_ptr, col_idx=col_idx, vals=vals,
+                    meta={"m_train": m_train, "m_test": m_test, "w0": 4.0, "rate": 0.99999})
+
+
 FULL = {
     "tiny_hinge": tiny_hinge,
     "dense_logistic": dense_logistic,

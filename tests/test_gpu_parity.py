@@ -522,6 +522,45 @@ def test_objective_rejects_bad_arguments():
     assert e.value.status in (api.INVALID_ARG, api.WORKSPACE_TOO_SMALL)
 
 
+# ------------------------------------------------------------------ the unbalanced-cluster experiment, small
+
+def test_weighted_average_beats_the_plain_average_on_unbalanced_chains():
+    """Section V, "Analog data", at a small size: eight fast chains and two with a fifth of the
+    steps, every chain started from the constant vector 4.  The slow chains have contracted less
+    towards the optimum, so averaging them in with full weight (plain averaging) must give a
+    worse held-out objective than the weights of Eq. 6; with equal step counts the two agree.
+    Every number is also checked against the oracle."""
+    w = wl.analog_binary(m_train=20000, m_test=4000, d=3000, n_fast=6000)
+    eta, lam = 0.05, 0.01                          # (1 - eta*lambda)^6000 = 0.05, ^1200 = 0.55
+    mt = w.meta["m_train"]
+    X = api.matrix_from_workload(w)
+    train = api.Matrix(mt, w.d, row_ptr=X.row_ptr[:mt + 1], col_idx=X.col_idx, vals=X.vals)
+    test = api.Matrix(w.m - mt, w.d, row_ptr=X.row_ptr[mt:], col_idx=X.col_idx, vals=X.vals)
+    y = torch.from_numpy(w.y).cuda()
+    w0 = torch.full((w.d,), float(w.meta["w0"]), dtype=torch.float32, device="cuda")
+    W = api.wpsgd_run_chains_from(train, y[:mt], w.n_steps, eta, lam, w.loss, w.seed, w_start=w0)
+    a = api.wpsgd_weights(w.n_steps, eta, lam)
+    assert a[-1] < 0.02 < 0.1 < a[0]               # the slow chains are almost switched off
+    v_wp = api.wpsgd_combine(W, a)
+    v_avg = api.wpsgd_combine(W, np.full(w.k, 1.0 / w.k))
+    obj_wp, err_wp = api.wpsgd_objective(test, y[mt:], v_wp, lam, w.loss).cpu().numpy()
+    obj_avg, err_avg = api.wpsgd_objective(test, y[mt:], v_avg, lam, w.loss).cpu().numpy()
+    assert obj_wp < 0.8 * obj_avg
+    assert err_wp <= err_avg
+
+    # the same numbers from the oracle
+    lo, hi = int(w.row_ptr[0]), int(w.row_ptr[mt])
+    Xo_train = orc.CSR(w.row_ptr[:mt + 1], w.col_idx[lo:hi], w.vals[lo:hi], w.d)
+    rp = w.row_ptr[mt:] - w.row_ptr[mt]
+    Xo_test = orc.CSR(rp, w.col_idx[hi:], w.vals[hi:], w.d)
+    Wo, _ = orc.run_chains(Xo_train, w.y[:mt], w.n_steps, eta, lam, w.loss, w.seed, w0_fill=float(w.meta["w0"]),
+                           csr_mode=orc.LAZY)
+    vo = orc.combine(Wo, orc.weights(w.n_steps, eta, lam))
+    assert np.linalg.norm(v_wp.cpu().numpy() - vo) / np.linalg.norm(vo) <= TOL
+    o_wp, e_wp = orc.objective(Xo_test, w.y[mt:], v_wp.cpu().numpy().astype(np.float64), lam, w.loss)
+    assert obj_wp == pytest.approx(o_wp, rel=1e-11) and abs(err_wp - e_wp) <= 1.0 / (w.m - mt)
+
+
 # ------------------------------------------------------------------ error paths
 
 def test_run_chains_rejects_bad_arguments():

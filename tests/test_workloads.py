@@ -62,3 +62,19 @@ def test_sparse_hinge_structure():
     assert set(np.unique(w.y)) == {-1.0, 1.0}
     again = wl.sparse_hinge(m=20000, d=1 << 16, k=16, n_median=300)
     assert np.array_equal(again.col_idx, w.col_idx) and np.array_equal(again.vals, w.vals)
+
+
+def test_analog_binary_follows_the_papers_recipe():
+    w = wl.analog_binary(m_train=3000, m_test=500, d=5000, n_fast=1000)
+    assert w.is_csr and w.m == 3500 and w.meta["m_train"] == 3000
+    lens = np.diff(w.row_ptr)
+    assert lens.min() == 5 and lens.max() == 10
+    assert w.n_steps.tolist() == [1000] * 8 + [200] * 2
+    for r in (0, 1, 17, 3499):
+        c = w.col_idx[w.row_ptr[r]:w.row_ptr[r + 1]].astype(np.int64)
+        v = w.vals[w.row_ptr[r]:w.row_ptr[r + 1]]
+        assert (np.diff(c) > 0).all() and c.max() < 5000
+        np.testing.assert_allclose(v, 1 / np.sqrt(len(c)), rtol=1e-6)          # binary features, unit row
+        score = sum(((i + 1) % 4) * (-1) ** (i + 1) for i in c.tolist())           # the paper's labelling rule
+        assert w.y[r] == (1.0 if score > 0 else -1.0)
+    assert 0.2 < (w.y > 0).mean() < 0.8
