@@ -466,7 +466,7 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);      // a scalar: registers are scarce here
     const int chain = a.order[blockIdx.x];
     const int64_t n = a.nsteps[blockIdx.x];
     const char *X = static_cast<const char *>(a.dense);
@@ -498,8 +498,9 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
         }
         double s_w = 1.0, eos_w = a.eta;
         const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
+        // out of line: the registers are full of model and row here, and this runs once per 64 steps
         auto window_rows = [&](int64_t w) {
-            return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(step0 + w * kWave + lane), m32);
+            return sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32);
         };
         uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
         TV zs_tab = (TV)0, cs_tab = (TV)0;     // per lane, label folded in: y*s_l (*log2 e), y*eta/s_{l+1}
@@ -528,9 +529,10 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
         const uint32_t slot0 = (uint32_t)__builtin_amdgcn_readfirstlane(
             (int)((uint32_t)(size_t)(lds_ptr)&stage[0][0][0] + (uint32_t)wave * (CHUNKS * kWave * 16)));
         auto request_chunk = [&](int c, u32x4 rx) {
-            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+            // the chunk's offset in the row rides in a scalar, so one vector register serves all chunks
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                          :
-                         : "s"(slot0 + c * (kWave * 16)), "v"(off0 + c * kChunkStride), "s"(rx)
+                         : "s"(slot0 + c * (kWave * 16)), "v"(off0), "s"(rx), "s"(c * kChunkStride)
                          : "memory", "m0");
         };
         auto take_chunk = [&](int c) {
