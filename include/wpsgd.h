@@ -43,6 +43,14 @@ typedef enum {
  *   logistic log(1 + exp(-y*yhat))   slope -y / (1 + exp(y*yhat))                            */
 typedef enum { WPSGD_HINGE = 0, WPSGD_LOGISTIC = 1 } wpsgd_loss;
 
+/* Which examples a chain visits.
+ *   STREAM  row = floor(word0 * m / 2^32) of a Philox4x32-10 stream keyed by (seed, chain, step):
+ *           independent draws with replacement from the whole data set (wpsgd_sample_indices).
+ *   SHARDS  Algorithm 1 as written: the examples are randomly partitioned among the k nodes and
+ *           each node walks its own part in random order, without replacement
+ *           (wpsgd_shard_indices).                                                             */
+typedef enum { WPSGD_SAMPLE_STREAM = 0, WPSGD_SAMPLE_SHARDS = 1 } wpsgd_sampling;
+
 /* Storage type of dense rows.  bfloat16 values are widened exactly to fp32 on load. */
 typedef enum { WPSGD_F32 = 0, WPSGD_BF16 = 1 } wpsgd_dtype;
 
@@ -103,11 +111,12 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
 /* The same from a common start vector and from inside the sample streams: chain i starts from
  * w_start (DEVICE, d entries fp32; NULL means zero) and takes the rows its stream names at steps
  * step_offsets[i] .. step_offsets[i] + n_steps[i] - 1 (HOST, k entries >= 0; NULL means zero).
- * With both NULL this is wpsgd_run_chains.  The experiments of the paper start every node from a
+ * With both NULL and sampling = WPSGD_SAMPLE_STREAM this is wpsgd_run_chains.  WPSGD_SAMPLE_SHARDS
+ * needs k <= m.  The experiments of the paper start every node from a
  * constant vector; restarting all chains from the weighted average every so many steps, each chain
  * continuing its own stream, is the periodic averaging of Section III (Deduction 2).            */
 int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
-                          double eta, double lambda, wpsgd_loss loss, uint64_t seed,
+                          double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
                           const float *w_start, const int64_t *step_offsets, float *W,
                           void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream);
 
@@ -156,6 +165,19 @@ int wpsgd_sample_indices(uint64_t seed, int chain, int64_t n0, int64_t count, in
                          int64_t *out_host);
 int wpsgd_sample_indices_device(uint64_t seed, int chain, int64_t n0, int64_t count, int64_t m,
                                 int64_t *out_device, void *stream);
+
+/* ---- sample order of Algorithm 1: random partition among k nodes, each node shuffles its part ----
+ * One keyed permutation pi of [0, m) shuffles all rows: a four-round Feistel network over 2h bits
+ * (h = max(1, ceil(bits(m-1)/2))), round r mapping (L, R) to (R, L xor (F_r(R) mod 2^h)) with
+ * F_r(R) = word 0 of Philox4x32-10(counter = (R, r, 0x5348524D, 0xFFFFFFFF), key = seed), applied
+ * again while the result is >= m.  Node i owns the permuted positions [floor(i*m/k), floor((i+1)*m/k))
+ * and visits them in order, starting over when it has seen them all:
+ *     row(i, n) = pi(lo_i + n mod m_i).
+ * Needs 1 <= k <= m < 2^32 and 0 <= chain < k.  HOST and DEVICE variants as above.             */
+int wpsgd_shard_indices(uint64_t seed, int chain, int k, int64_t n0, int64_t count, int64_t m,
+                        int64_t *out_host);
+int wpsgd_shard_indices_device(uint64_t seed, int chain, int k, int64_t n0, int64_t count, int64_t m,
+                               int64_t *out_device, void *stream);
 
 /* ---- diagnostics ---- */
 /* Streaming ceiling probe (not a step of the method): `groups` workgroups of 256 threads each read

@@ -54,6 +54,7 @@ def lib():
         L.oracle_philox4x32_10.argtypes = [pu32, pu32, pu32]
         L.oracle_philox4x32_10.restype = None
         L.oracle_sample_indices.argtypes = [ctypes.c_uint64, i64, i64, i64, i64, pi64]
+        L.oracle_shard_indices.argtypes = [ctypes.c_uint64, i64, i64, i64, i64, i64, pi64]
         L.oracle_sgd_dense.argtypes = [vp, i32, i64, i64, pf32, pi64, i64, f64, f64, i32, pf64, pf64]
         L.oracle_sgd_csr.argtypes = [pi64, pi32, pf32, i64, i64, pf32, pi64, i64, f64, f64, i32, i32, pf64, pf64]
         L.oracle_weights_rate.argtypes = [i64, pi64, f64, pf64]
@@ -78,6 +79,15 @@ def philox4x32_10(ctr, key):
     assert c.shape == (4,) and k.shape == (2,)
     out = np.zeros(4, dtype=np.uint32)
     lib().oracle_philox4x32_10(_p(c, ctypes.c_uint32), _p(k, ctypes.c_uint32), _p(out, ctypes.c_uint32))
+    return out
+
+
+def shard_indices(seed, chain, k, n0, count, m):
+    """Rows node `chain` of k visits at steps n0.. under partition-and-shuffle sampling (Algorithm 1)."""
+    out = np.zeros(max(int(count), 0), dtype=np.int64)
+    _check(lib().oracle_shard_indices(ctypes.c_uint64(int(seed)), ctypes.c_int64(int(chain)), ctypes.c_int64(int(k)),
+                                      ctypes.c_int64(int(n0)), ctypes.c_int64(int(count)), ctypes.c_int64(int(m)),
+                                      _p(out, ctypes.c_int64)), "shard_indices")
     return out
 
 

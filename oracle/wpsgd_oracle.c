@@ -89,6 +89,64 @@ int oracle_sample_indices(uint64_t seed, int64_t chain, int64_t n0, int64_t coun
 }
 
 /* ------------------------------------------------------------------ */
+/* Sampling as Algorithm 1 states it: "randomly partition the          */
+/* examples, giving each node its share; randomly shuffle the data on  */
+/* each node; get the n-th example".  Counter-based version: a keyed   */
+/* permutation P of {0..m-1} shuffles all rows once; node i of k owns   */
+/* the positions lo_i = floor(i*m/k) .. floor((i+1)*m/k) - 1 of the     */
+/* shuffled order and reads them one after the other (wrapping round   */
+/* if it is asked for more steps than it has rows):                    */
+/*     row(i, n) = P(lo_i + n mod m_i).                                */
+/* P is a 4-round Feistel network on 2h-bit numbers, h = ceil(b/2) with */
+/* b the bit length of m-1 (h >= 1); round r sends (L, R) to            */
+/* (R, L xor low_h(F_r(R))) with F_r(R) the first output word of        */
+/* Philox4x32-10 on counter (R, r, 0x5348524D, 0xFFFFFFFF) and the      */
+/* seed as key.  A result >= m is fed through the network again        */
+/* (cycle walking), which keeps P a permutation of {0..m-1}.           */
+/* ------------------------------------------------------------------ */
+static uint32_t shuffle_position(uint64_t seed, uint32_t pos, uint32_t m)
+{
+    int bits = 0;
+    for (uint32_t t = m - 1; t; t >>= 1) ++bits;
+    int h = (bits + 1) / 2;
+    if (h < 1) h = 1;
+    const uint32_t low = ((uint32_t)1 << h) - 1u;
+    uint32_t key[2] = { (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32) };
+    uint32_t x = pos;
+    for (;;) {
+        uint32_t left = x >> h, right = x & low;
+        for (uint32_t round = 0; round < 4; ++round) {
+            uint32_t ctr[4] = { right, round, 0x5348524Du, 0xFFFFFFFFu };
+            uint32_t out[4];
+            oracle_philox4x32_10(ctr, key, out);
+            uint32_t next_right = left ^ (out[0] & low);
+            left = right;
+            right = next_right;
+        }
+        x = (left << h) | right;
+        if (x < m) return x;
+    }
+}
+
+int64_t oracle_shard_index(uint64_t seed, int64_t chain, int64_t k, uint64_t n, int64_t m)
+{
+    uint64_t lo = ((uint64_t)chain * (uint64_t)m) / (uint64_t)k;
+    uint64_t hi = ((uint64_t)(chain + 1) * (uint64_t)m) / (uint64_t)k;
+    uint64_t own = hi - lo;
+    return (int64_t)shuffle_position(seed, (uint32_t)(lo + n % own), (uint32_t)m);
+}
+
+int oracle_shard_indices(uint64_t seed, int64_t chain, int64_t k, int64_t n0, int64_t count,
+                         int64_t m, int64_t *out)
+{
+    if (!out || count < 0 || n0 < 0 || k < 1 || chain < 0 || chain >= k) return ORACLE_BAD_ARG;
+    if (m < 1 || m > 0xffffffffLL || k > m) return ORACLE_BAD_ARG;
+    for (int64_t t = 0; t < count; ++t)
+        out[t] = oracle_shard_index(seed, chain, k, (uint64_t)(n0 + t), m);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
 /* Stored value -> double, exactly.                                    */
 /* ------------------------------------------------------------------ */
 static double bf16_to_double(uint16_t h)

@@ -18,6 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libwpsgd.so")
 
 HINGE, LOGISTIC = 0, 1
+SAMPLE_STREAM, SAMPLE_SHARDS = 0, 1
 F32, BF16 = 0, 1
 OK, INVALID_ARG, HIP_ERROR, WORKSPACE_TOO_SMALL, UNSUPPORTED = 0, -1, -2, -3, -4
 
@@ -26,7 +27,7 @@ EXPORTS = [
     "wpsgd_benefit_margin", "wpsgd_combine_workspace", "wpsgd_combine", "wpsgd_sample_indices",
     "wpsgd_sample_indices_device", "wpsgd_strerror", "wpsgd_last_hip_error", "wpsgd_describe_plan",
     "wpsgd_stream_rows", "wpsgd_objective_workspace", "wpsgd_objective",
-    "wpsgd_run_chains_from",
+    "wpsgd_run_chains_from", "wpsgd_shard_indices", "wpsgd_shard_indices_device",
 ]
 
 
@@ -68,7 +69,9 @@ def load():
     L.wpsgd_run_chains_workspace.argtypes = [pm, ci, ci, pp]
     L.wpsgd_run_chains_workspace.restype = sz
     L.wpsgd_run_chains.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, sz, pp, vp]
-    L.wpsgd_run_chains_from.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, vp, vp, sz, pp, vp]
+    L.wpsgd_run_chains_from.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, ci, vp, vp, vp, vp, sz, pp, vp]
+    L.wpsgd_shard_indices.argtypes = [u64, ci, ci, i64, i64, i64, vp]
+    L.wpsgd_shard_indices_device.argtypes = [u64, ci, ci, i64, i64, i64, vp, vp]
     L.wpsgd_weights.argtypes = [ci, vp, f64, f64, vp]
     L.wpsgd_weights_rate.argtypes = [ci, vp, f64, vp]
     L.wpsgd_benefit_margin.argtypes = [ci, vp, f64, vp]
@@ -196,7 +199,7 @@ def wpsgd_run_chains(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
 
 
 def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
-                          w_start: Optional[torch.Tensor] = None, step_offsets=None,
+                          w_start: Optional[torch.Tensor] = None, step_offsets=None, sampling=0,
                           W: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                           plan=None, stream=None) -> torch.Tensor:
     """wpsgd_run_chains from a common start vector (d float32 on the GPU, or None for zero) and
@@ -220,7 +223,7 @@ def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, s
         need = load().wpsgd_run_chains_workspace(ctypes.byref(cm), k, int(loss), pl)
         workspace = _workspace(need, dev)
     rc = load().wpsgd_run_chains_from(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, float(eta),
-                                      float(lam), int(loss), int(seed),
+                                      float(lam), int(loss), int(seed), int(sampling),
                                       w_start.data_ptr() if w_start is not None else None,
                                       off.ctypes.data if off is not None else None, W.data_ptr(),
                                       workspace.data_ptr(), workspace.numel(), pl, _stream(stream))
@@ -307,6 +310,23 @@ def wpsgd_sample_indices(seed, chain, n0, count, m) -> np.ndarray:
                                      out.ctypes.data)
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_sample_indices")
+    return out
+
+
+def wpsgd_shard_indices(seed, chain, k, n0, count, m) -> np.ndarray:
+    out = np.zeros(max(int(count), 0), dtype=np.int64)
+    rc = load().wpsgd_shard_indices(int(seed), int(chain), int(k), int(n0), int(count), int(m), out.ctypes.data)
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_shard_indices")
+    return out
+
+
+def wpsgd_shard_indices_device(seed, chain, k, n0, count, m, device="cuda", stream=None) -> torch.Tensor:
+    out = torch.empty(max(int(count), 0), dtype=torch.int64, device=device)
+    rc = load().wpsgd_shard_indices_device(int(seed), int(chain), int(k), int(n0), int(count), int(m),
+                                           out.data_ptr(), _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_shard_indices_device")
     return out
 
 

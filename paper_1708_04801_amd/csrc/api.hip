@@ -156,15 +156,21 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
 
 static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
+// shuffled row order of partition-and-shuffle sampling (always reserved: the workspace query does
+// not know which sampling a call will ask for)
+static size_t perm_bytes(int64_t m) { return align256((size_t)m * sizeof(uint32_t)); }
+
 static size_t state_elem_bytes(wpsgd_loss loss)
 {
     return loss == WPSGD_HINGE ? sizeof(double) : sizeof(float);
 }
 
-// workspace header: chain order, then step counts and stream offsets in that order
+// workspace header: chain order, then (in that order) step counts, stream offsets, and three
+// 32-bit numbers per chain describing its share under partition-and-shuffle sampling
 static size_t header_bytes(int k)
 {
-    return align256((size_t)k * sizeof(int32_t)) + 2 * align256((size_t)k * sizeof(int64_t));
+    return align256((size_t)k * sizeof(int32_t)) + 2 * align256((size_t)k * sizeof(int64_t)) +
+           align256((size_t)k * 3 * sizeof(uint32_t));
 }
 
 // Host arrays (chain order, step counts, weights) reach the device through a small ring of pinned
@@ -243,7 +249,7 @@ size_t wpsgd_run_chains_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss,
     if (resolve_plan(X, loss, plan, &p) != WPSGD_OK) return 0;
     // Always room for the model vectors in HBM: which kernel runs also depends on eta*lambda,
     // which this query does not see.
-    return header_bytes(k) + align256((size_t)k * (size_t)X->d * state_elem_bytes(loss));
+    return header_bytes(k) + perm_bytes(X->m) + align256((size_t)k * (size_t)X->d * state_elem_bytes(loss));
 }
 
 int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *plan,
@@ -270,18 +276,20 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
                      double eta, double lambda, wpsgd_loss loss, uint64_t seed, float *W,
                      void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream)
 {
-    return wpsgd_run_chains_from(X, y, k, n_steps, eta, lambda, loss, seed, nullptr, nullptr, W, workspace,
-                                 workspace_bytes, plan, stream);
+    return wpsgd_run_chains_from(X, y, k, n_steps, eta, lambda, loss, seed, WPSGD_SAMPLE_STREAM, nullptr, nullptr, W,
+                                 workspace, workspace_bytes, plan, stream);
 }
 
 int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
-                          double eta, double lambda, wpsgd_loss loss, uint64_t seed,
+                          double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
                           const float *w_start, const int64_t *step_offsets, float *W,
                           void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream)
 {
     int rc = check_matrix(X);
     if (rc != WPSGD_OK) return rc;
     if (!y || !W) return WPSGD_INVALID_ARG;
+    if (sampling != WPSGD_SAMPLE_STREAM && sampling != WPSGD_SAMPLE_SHARDS) return WPSGD_INVALID_ARG;
+    if (sampling == WPSGD_SAMPLE_SHARDS && (int64_t)k > X->m) return WPSGD_INVALID_ARG;     // a node without examples
     rc = check_steps(k, n_steps);
     if (rc != WPSGD_OK) return rc;
     if (step_offsets)
@@ -294,7 +302,7 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     for (int i = 0; i < k; ++i) max_steps = std::max(max_steps, n_steps[i]);
     rc = resolve_plan(X, loss, plan, &p, 1.0 - eta * lambda, max_steps);
     if (rc != WPSGD_OK) return rc;
-    const size_t need = header_bytes(k) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
+    const size_t need = header_bytes(k) + perm_bytes(X->m) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
     if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
     if (workspace_bytes < need) return WPSGD_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -311,16 +319,25 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     const size_t steps_bytes = align256((size_t)k * sizeof(int64_t));
     int64_t *sorted_steps = reinterpret_cast<int64_t *>(header.data() + order_bytes);
     int64_t *sorted_offsets = reinterpret_cast<int64_t *>(header.data() + order_bytes + steps_bytes);
+    uint32_t *shard = reinterpret_cast<uint32_t *>(header.data() + order_bytes + 2 * steps_bytes);
     for (int b = 0; b < k; ++b) {
         sorted_steps[b] = n_steps[order[b]];
         sorted_offsets[b] = step_offsets ? step_offsets[order[b]] : 0;
+        if (sampling == WPSGD_SAMPLE_SHARDS) {
+            const uint64_t lo = (uint64_t)order[b] * (uint64_t)X->m / (uint64_t)k;
+            const uint64_t hi = ((uint64_t)order[b] + 1) * (uint64_t)X->m / (uint64_t)k;
+            shard[b] = (uint32_t)lo;
+            shard[k + b] = (uint32_t)(hi - lo);
+            shard[2 * k + b] = (uint32_t)((uint64_t)sorted_offsets[b] % (hi - lo));
+        }
     }
 
     char *ws = static_cast<char *>(workspace);
     int32_t *order_dev = reinterpret_cast<int32_t *>(ws);
     int64_t *steps_dev = reinterpret_cast<int64_t *>(ws + order_bytes);
     int64_t *offsets_dev = reinterpret_cast<int64_t *>(ws + order_bytes + steps_bytes);
-    void *state_dev = ws + header_bytes(k);
+    uint32_t *perm_dev = reinterpret_cast<uint32_t *>(ws + header_bytes(k));
+    void *state_dev = ws + header_bytes(k) + perm_bytes(X->m);
     rc = upload(ws, header.data(), header.size(), s);
     if (rc != WPSGD_OK) return rc;
 
@@ -342,6 +359,13 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     a.rho = 1.0 - eta * lambda;
     a.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);
     a.seed_hi = (uint32_t)(seed >> 32);
+    a.perm = nullptr;
+    if (sampling == WPSGD_SAMPLE_SHARDS) {
+        hipError_t pe = launch_permute_rows(a.seed_lo, a.seed_hi, (uint32_t)X->m, perm_dev, s);
+        if (pe != hipSuccess) return hip_fail(pe);
+        a.perm = perm_dev;
+        a.shard = reinterpret_cast<const uint32_t *>(ws + order_bytes + 2 * steps_bytes);
+    }
     a.W = W;
     a.state = state_dev;
 
@@ -476,7 +500,31 @@ int wpsgd_sample_indices_device(uint64_t seed, int chain, int64_t n0, int64_t co
     if (chain < 0 || n0 < 0 || count < 0 || m < 1 || m > 0xFFFFFFFFLL) return WPSGD_INVALID_ARG;
     if (count > 0 && !out_device) return WPSGD_INVALID_ARG;
     hipError_t e = launch_sample_rows((uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32),
-                                      (uint32_t)chain, n0, count, (uint32_t)m, out_device,
+                                      (uint32_t)chain, n0, count, (uint32_t)m, 0u, out_device,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
+int wpsgd_shard_indices(uint64_t seed, int chain, int k, int64_t n0, int64_t count, int64_t m,
+                        int64_t *out_host)
+{
+    if (chain < 0 || k < 1 || chain >= k || n0 < 0 || count < 0 || m < 1 || m > 0xFFFFFFFFLL || (int64_t)k > m)
+        return WPSGD_INVALID_ARG;
+    if (count > 0 && !out_host) return WPSGD_INVALID_ARG;
+    for (int64_t t = 0; t < count; ++t)
+        out_host[t] = (int64_t)shard_row((uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), (uint32_t)chain,
+                                         (uint32_t)k, (uint64_t)(n0 + t), (uint32_t)m);
+    return WPSGD_OK;
+}
+
+int wpsgd_shard_indices_device(uint64_t seed, int chain, int k, int64_t n0, int64_t count, int64_t m,
+                               int64_t *out_device, void *stream)
+{
+    if (chain < 0 || k < 1 || chain >= k || n0 < 0 || count < 0 || m < 1 || m > 0xFFFFFFFFLL || (int64_t)k > m)
+        return WPSGD_INVALID_ARG;
+    if (count > 0 && !out_device) return WPSGD_INVALID_ARG;
+    hipError_t e = launch_sample_rows((uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32),
+                                      (uint32_t)chain, n0, count, (uint32_t)m, (uint32_t)k, out_device,
                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? WPSGD_OK : hip_fail(e);
 }

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kWave) void chain_csr_kernel(ChainArgs a)
     const int64_t step0 = a.step0[blockIdx.x];
 
     RowWindow win;
-    win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
+    win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m, a.perm, (uint32_t)a.k);
     double s = 1.0, inv_s = 1.0;
     const double rho = a.rho, inv_rho = 1.0 / a.rho, eta = a.eta;
 
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
     float y_b;
     TV zs_tab = (TV)0, cs_tab = (TV)0;
     auto load_window = [&](int64_t w, int64_t &lo, int &len, float &y) {
-        const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32);
+        const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32, a.perm, (uint32_t)a.k);
         const int64_t p0 = a.row_ptr[row], p1 = a.row_ptr[(int64_t)row + 1];
         lo = p0;
         len = (int)(p1 - p0);

@@ -217,7 +217,7 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
         int len_a, len_b;
         float y_a, y_b;
         auto load_window = [&](int64_t w, int64_t &lo, int &len, float &y) {
-            const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32);
+            const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32, a.perm, (uint32_t)a.k);
             const int64_t p0 = a.row_ptr[row], p1 = a.row_ptr[(int64_t)row + 1];
             lo = p0;
             len = (int)(p1 - p0);

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(NT) void chain_dense_mem_kernel(ChainArgs a)
     const int64_t step0 = a.step0[blockIdx.x];
 
     RowWindow win;
-    win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
+    win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m, a.perm, (uint32_t)a.k);
     double s = 1.0, inv_s = 1.0;
     const double rho = a.rho, inv_rho = 1.0 / a.rho, eta = a.eta;
     int parity = 0;

@@ -139,7 +139,26 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         double s_w = 1.0, eos_w = a.eta;     // scale and eta/scale at the start of the window
 
         const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
+        // Partition-and-shuffle sampling reads the tabulated shuffled order; the lane's position in
+        // its chain's share advances by 64 (mod the share size) from window to window, so no
+        // division sits in the loop.  Windows are asked for in order: 0, 1, 2, ...
+        uint32_t shard_lo = 0, shard_len = 1, shard_inc = 0, shard_pos = 0;
+        if (a.perm) {
+            shard_lo = a.shard[blockIdx.x];
+            shard_len = a.shard[a.k + blockIdx.x];
+            const uint32_t pos0 = a.shard[2 * a.k + blockIdx.x], room = shard_len - pos0;
+            shard_inc = (uint32_t)kWave % shard_len;
+            shard_pos = (uint32_t)lane < room ? pos0 + (uint32_t)lane : ((uint32_t)lane - room) % shard_len;
+        }
         auto window_rows = [&](int64_t w) {
+            if (a.perm) {
+                const uint32_t *p = a.perm + ((uint64_t)shard_lo + shard_pos);
+                uint32_t r;   // a load the compiler does not count: nothing outside this branch may wait for it
+                asm volatile("global_load_dword %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(r) : "v"(p) : "memory");
+                const uint32_t t = shard_pos + shard_inc;                 // may wrap past 2^32: then it is past the share too
+                shard_pos = (t < shard_pos || t >= shard_len) ? t - shard_len : t;
+                return r;
+            }
             return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(step0 + w * kWave + lane), m32);
         };
         uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
@@ -394,7 +413,7 @@ __global__ __launch_bounds__(NT) void chain_dense_wide_kernel(ChainArgs a)
                         eos_w = a.eta;
                     }
                 }
-                rows = sample_window(a.seed_lo, a.seed_hi, (uint32_t)chain, step0 + step, (uint32_t)a.m);
+                rows = sample_window(a.seed_lo, a.seed_hi, (uint32_t)chain, step0 + step, (uint32_t)a.m, a.perm, (uint32_t)a.k);
                 const double sl = s_w * rho_pow, el = eos_w * inv_rho_pow1;
                 if constexpr (LOSS == kLossHinge) {
                     zs_tab = sl;
@@ -500,7 +519,7 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
         const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
         // out of line: the registers are full of model and row here, and this runs once per 64 steps
         auto window_rows = [&](int64_t w) {
-            return sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32);
+            return sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32, a.perm, (uint32_t)a.k);
         };
         uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
         TV zs_tab = (TV)0, cs_tab = (TV)0;     // per lane, label folded in: y*s_l (*log2 e), y*eta/s_{l+1}

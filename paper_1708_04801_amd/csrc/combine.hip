@@ -119,17 +119,38 @@ hipError_t launch_combine(const float *W, const double *a_dev, int k, int64_t d,
 // chain kernels read (so this kernel checks their generator, not a copy of it).
 __global__ __launch_bounds__(kWave) void sample_rows_kernel(uint32_t seed_lo, uint32_t seed_hi,
                                                             uint32_t chain, int64_t n0,
-                                                            int64_t count, uint32_t m, int64_t *out)
+                                                            int64_t count, uint32_t m, uint32_t shard_k,
+                                                            int64_t *out)
 {
-    RowWindow win;
-    win.init(seed_lo, seed_hi, chain, m);
     const int64_t per = (count + gridDim.x - 1) / gridDim.x;
     const int64_t t0 = (int64_t)blockIdx.x * per;
     const int64_t t1 = (t0 + per < count) ? t0 + per : count;
+    if (shard_k) {     // partition-and-shuffle order, evaluated directly
+        for (int64_t t = t0 + threadIdx.x; t < t1; t += kWave)
+            out[t] = (int64_t)shard_row(seed_lo, seed_hi, chain, shard_k, (uint64_t)(n0 + t), m);
+        return;
+    }
+    RowWindow win;
+    win.init(seed_lo, seed_hi, chain, m);
     for (int64_t t = t0; t < t1; ++t) {
         const uint32_t row = win.get(n0 + t);
         if (threadIdx.x == 0) out[t] = (int64_t)row;
     }
+}
+
+// The shuffled row order pi(0), .., pi(m-1) of partition-and-shuffle sampling, one entry per thread.
+__global__ __launch_bounds__(256) void permute_rows_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t m,
+                                                           uint32_t half, uint32_t *perm)
+{
+    const uint64_t pos = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (pos < m) perm[pos] = permute_row((uint32_t)pos, m, half, seed_lo, seed_hi);
+}
+
+hipError_t launch_permute_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t m, uint32_t *perm, hipStream_t s)
+{
+    const unsigned grid = (unsigned)(((uint64_t)m + 255) / 256);
+    hipLaunchKernelGGL(permute_rows_kernel, dim3(grid), dim3(256), 0, s, seed_lo, seed_hi, m, feistel_half_bits(m), perm);
+    return hipGetLastError();
 }
 
 // Streaming ceiling probe: `groups` workgroups each read `rows_per_group` rows of a dense matrix
@@ -198,12 +219,12 @@ hipError_t launch_stream_rows(const void *X, int64_t row_stride, uint32_t row_by
 }
 
 hipError_t launch_sample_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, int64_t n0,
-                              int64_t count, uint32_t m, int64_t *out, hipStream_t s)
+                              int64_t count, uint32_t m, uint32_t shard_k, int64_t *out, hipStream_t s)
 {
     if (count == 0) return hipSuccess;
     const unsigned grid = (unsigned)((count + 255) / 256 < 1024 ? (count + 255) / 256 : 1024);
     hipLaunchKernelGGL(sample_rows_kernel, dim3(grid), dim3(kWave), 0, s, seed_lo, seed_hi, chain, n0,
-                       count, m, out);
+                       count, m, shard_k, out);
     return hipGetLastError();
 }
 

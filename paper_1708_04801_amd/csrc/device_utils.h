@@ -49,26 +49,83 @@ __host__ __device__ inline uint32_t sample_row(uint32_t seed_lo, uint32_t seed_h
     return mul_hi_u32(r0, m);
 }
 
-// Rows of the 64 steps starting at `base`, one per lane.  Kept out of line: it runs once per 64
-// steps, and inlining its ~80 integer instructions at every use bloats the loops around it.
+// ---------------------------------------------------------------------------------------------
+// Sampling as Algorithm 1 writes it: the examples are randomly partitioned among the k nodes and
+// every node walks its own part in random order.  Kept counter-based: one keyed permutation pi
+// of [0, m) (a four-round Feistel network over 2*half bits whose round function is Philox, with
+// cycle walking to stay inside [0, m)) shuffles all rows; node i owns the permuted positions
+// [floor(i*m/k), floor((i+1)*m/k)) and visits them in order, starting over when it has seen them
+// all.  Row of node i at step n:  pi(lo_i + n mod m_i).
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline uint32_t feistel_half_bits(uint32_t m)
+{
+    uint32_t bits = 0;                       // bits needed for m-1
+    for (uint32_t x = m - 1; x != 0; x >>= 1) ++bits;
+    const uint32_t half = (bits + 1) / 2;
+    return half == 0 ? 1u : half;
+}
+
+__host__ __device__ inline uint32_t permute_row(uint32_t x, uint32_t m, uint32_t half, uint32_t seed_lo,
+                                                uint32_t seed_hi)
+{
+    const uint32_t mask = (1u << half) - 1u;
+    do {
+        uint32_t L = x >> half, Rr = x & mask;
+#pragma unroll
+        for (uint32_t r = 0; r < 4; ++r) {
+            const uint32_t f = philox4x32_10_word0(Rr, r, 0x5348524Du, 0xFFFFFFFFu, seed_lo, seed_hi) & mask;
+            const uint32_t t = L ^ f;
+            L = Rr;
+            Rr = t;
+        }
+        x = (L << half) | Rr;
+    } while (x >= m);                        // the network permutes [0, 4^half); walk the cycle back into [0, m)
+    return x;
+}
+
+__host__ __device__ inline uint32_t shard_row(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, uint32_t k,
+                                              uint64_t step, uint32_t m)
+{
+    const uint64_t lo = ((uint64_t)chain * m) / k, hi = ((uint64_t)(chain + 1) * m) / k;
+    const uint64_t len = hi - lo;            // >= 1 because k <= m
+    return permute_row((uint32_t)(lo + step % len), m, feistel_half_bits(m), seed_lo, seed_hi);
+}
+
+// Position in the shuffled order of the row node `chain` of k visits at `step` (see above).
+__host__ __device__ inline uint32_t shard_position(uint32_t chain, uint32_t k, uint64_t step, uint32_t m)
+{
+    const uint64_t lo = ((uint64_t)chain * m) / k, hi = ((uint64_t)(chain + 1) * m) / k;
+    return (uint32_t)(lo + step % (hi - lo));
+}
+
+// Rows of the 64 steps starting at `base`, one per lane.  perm == nullptr: the with-replacement
+// stream.  Otherwise partition-and-shuffle sampling over k nodes, with perm the shuffled order
+// pi(0..m-1) tabulated beforehand (the chain kernels read it instead of evaluating pi).  Kept out
+// of line: it runs once per 64 steps, and inlining its integer code at every use bloats the loops
+// around it.
 __device__ __attribute__((noinline)) inline uint32_t sample_window(uint32_t seed_lo, uint32_t seed_hi,
                                                                    uint32_t chain, int64_t base,
-                                                                   uint32_t m)
+                                                                   uint32_t m, const uint32_t *perm = nullptr,
+                                                                   uint32_t k = 1)
 {
-    return sample_row(seed_lo, seed_hi, chain, (uint64_t)(base + (int)(threadIdx.x & (kWave - 1))), m);
+    const uint64_t step = (uint64_t)(base + (int)(threadIdx.x & (kWave - 1)));
+    if (perm) return perm[shard_position(chain, k, step, m)];
+    return sample_row(seed_lo, seed_hi, chain, step, m);
 }
 
 // One wave's window onto a chain's sample stream: lane l holds the row of step base+l.
 // get(step) must be called with a wave-uniform step; it refills the window (64 Philox
 // evaluations, one per lane) whenever the step leaves it.
 struct RowWindow {
-    uint32_t seed_lo, seed_hi, chain, m;
+    uint32_t seed_lo, seed_hi, chain, m, k;
+    const uint32_t *perm;
     int64_t base;
     uint32_t rows;
 
-    __device__ void init(uint32_t slo, uint32_t shi, uint32_t c, uint32_t mm)
+    __device__ void init(uint32_t slo, uint32_t shi, uint32_t c, uint32_t mm, const uint32_t *pm = nullptr,
+                         uint32_t kk = 1)
     {
-        seed_lo = slo; seed_hi = shi; chain = c; m = mm;
+        seed_lo = slo; seed_hi = shi; chain = c; m = mm; perm = pm; k = kk;
         base = -1;
         rows = 0;
     }
@@ -77,7 +134,7 @@ struct RowWindow {
         const int64_t b = step & ~(int64_t)(kWave - 1);
         if (b != base) {
             base = b;
-            rows = sample_window(seed_lo, seed_hi, chain, b, m);
+            rows = sample_window(seed_lo, seed_hi, chain, b, m, perm, k);
         }
         return (uint32_t)__builtin_amdgcn_readlane((int)rows, (int)(step & (kWave - 1)));
     }

@@ -27,6 +27,10 @@ struct ChainArgs {
     const int64_t *nsteps;    // DEVICE, k entries: steps of that chain
     const int64_t *step0;     // DEVICE, k entries: position in that chain's sample stream of its first step
     const float *w_start;     // DEVICE, d entries: every chain starts from this vector; NULL: from zero
+    const uint32_t *perm;     // DEVICE, m entries: shuffled row order for partition-and-shuffle sampling;
+                              // NULL: the with-replacement stream
+    const uint32_t *shard;    // DEVICE, 3k entries when perm is set: for workgroup b, its chain's first
+                              // position shard[b], share size shard[k+b], and step0 mod size shard[2k+b]
     // hyper-parameters (fp64 on purpose: (1-eta*lambda)^n must not be compounded in fp32)
     double eta, rho;          // rho = 1 - eta*lambda
     uint32_t seed_lo, seed_hi;
@@ -68,7 +72,8 @@ int64_t objective_grid(int64_t m);
 size_t objective_partials_bytes(int64_t m);
 hipError_t launch_objective(const ChainArgs &a, int dtype, int vec, int loss, const float *w, double lambda,
                             double *partials, double *out, hipStream_t s);
+hipError_t launch_permute_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t m, uint32_t *perm, hipStream_t s);
 hipError_t launch_sample_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, int64_t n0,
-                              int64_t count, uint32_t m, int64_t *out, hipStream_t s);
+                              int64_t count, uint32_t m, uint32_t shard_k, int64_t *out, hipStream_t s);
 
 }  // namespace wpsgd

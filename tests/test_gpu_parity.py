@@ -464,6 +464,49 @@ def test_run_chains_from_rejects_negative_offsets():
     assert e.value.status == api.INVALID_ARG
 
 
+# ------------------------------------------------------------------ partition-and-shuffle sampling
+
+def test_device_shard_stream_is_bit_exact():
+    for seed, m, k, chain in [(0, 4096, 4, 1), (3, 1000003, 128, 127), (11, 65537, 9, 0), (5, 70, 64, 33)]:
+        for n0 in (0, 63, 1000):
+            got = api.wpsgd_shard_indices_device(seed, chain, k, n0, 500, m).cpu().numpy()
+            assert np.array_equal(got, orc.shard_indices(seed, chain, k, n0, 500, m))
+
+
+def _check_shards(w, plan, label):
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    W = api.wpsgd_run_chains_from(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed, sampling=api.SAMPLE_SHARDS, plan=plan)
+    Xo = orc.CSR(w.row_ptr, w.col_idx, w.vals, w.d) if w.is_csr else orc.Dense(w.dense)
+    Wg = W.cpu().numpy().astype(np.float64)
+    for i in range(w.k):
+        idx = orc.shard_indices(w.seed, i, w.k, 0, int(w.n_steps[i]), w.m)
+        wo, closest = orc.sgd(Xo, w.y, idx, w.eta, w.lam, w.loss)
+        if w.loss == wl.HINGE and w.n_steps[i] > 0:
+            assert closest > KINK, f"{label}: a hinge step sits on the kink"
+        err = np.linalg.norm(Wg[i] - wo) / max(np.linalg.norm(wo), 1e-300)
+        assert err <= TOL, f"{label}: chain {i} rel L2 {err:.3e}"
+
+
+@pytest.mark.parametrize("d,plan", [(64, None), (300, None), (4096, None), (5000, {"state_in_hbm": 1}), (20000, None),
+                                    (20000, {"rows": 3})])
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_dense_chains_on_shuffled_shards(d, plan, loss):
+    rng = np.random.default_rng(d + 5 * loss)
+    m = 301
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = np.array([130, 0, 75, 200], dtype=np.int64)          # 200 > 75 rows per node: a second pass over the share
+    w = wl.Workload("shards_dense", loss, 0.3, 1e-2, 21, n, y, m, d, dense=X)
+    _check_shards(w, plan, f"dense d={d} {plan}")
+
+
+@pytest.mark.parametrize("plan", SPARSE_PLANS)
+def test_sparse_chains_on_shuffled_shards(plan):
+    w = wl.sparse_hinge(m=3000, d=1 << 14, k=5, n_median=150)
+    _check_shards(w, plan, f"sparse {plan}")
+
+
 # ------------------------------------------------------------------ objective and error rate
 
 def _check_objective(w, wvec, lam, label):

@@ -67,6 +67,16 @@ def test_host_sample_stream_equals_oracle_bit_for_bit():
             assert np.array_equal(got, orc.sample_indices(seed, chain, n0, 200, m))
 
 
+def test_host_shard_stream_equals_oracle_bit_for_bit():
+    for seed, m, k in [(0, 4096, 4), (77, 1000003, 10), (2 ** 64 - 1, 65537, 64), (5, 1, 1), (9, 17, 17)]:
+        for chain in {0, k // 2, k - 1}:
+            for n0 in (0, 12345):
+                got = api.wpsgd_shard_indices(seed, chain, k, n0, 300, m)
+                assert np.array_equal(got, orc.shard_indices(seed, chain, k, n0, 300, m))
+    with pytest.raises(api.WpsgdError):
+        api.wpsgd_shard_indices(0, 0, 5, 0, 1, 4)          # more nodes than rows
+
+
 def test_argument_errors_are_reported_not_crashed():
     for bad in [lambda: api.wpsgd_weights([1, -2], 0.1, 0.1), lambda: api.wpsgd_weights([1], 0.0, 0.1),
                 lambda: api.wpsgd_weights([1], 1.0, 1.0), lambda: api.wpsgd_weights([1], 0.1, -0.1),
@@ -115,10 +125,11 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
 
 
 def test_workspace_sizes():
-    # chain order + step counts + stream offsets (256-byte slots) + room for the model vectors in HBM
-    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 768 + 4 * 64 * 8
+    # chain order + step counts + stream offsets + share descriptions (256-byte slots) + shuffled row order (4 bytes a row)
+    # + room for the model vectors in HBM
+    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 1024 + 4096 * 4 + 4 * 64 * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.HINGE)
     assert ws >= 128 * (1 << 20) * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.LOGISTIC)
-    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096
+    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 512
     assert api.wpsgd_combine_workspace(64, 4096) == 512

@@ -59,6 +59,51 @@ def test_index_stream_from_an_offset_is_a_slice_of_the_stream():
         assert np.array_equal(orc.sample_indices(9, 3, n0, 40, 1000), whole[n0:n0 + 40])
 
 
+# ------------------------------------------------ partition-and-shuffle sampling (Algorithm 1 as written)
+
+@pytest.mark.parametrize("m,k", [(1, 1), (2, 1), (2, 2), (3, 2), (5, 5), (16, 3), (17, 4), (64, 64), (1000, 7),
+                                 (4097, 10), (65536, 9), (65537, 8)])
+def test_shards_partition_the_rows_and_every_node_sees_its_share_once(m, k):
+    """"Randomly partition the examples ... randomly shuffle the data on each node": over its
+    first m_i steps a node sees m_i different rows, the nodes' rows are disjoint, together they
+    are every row, and the share sizes differ by at most one."""
+    seen = []
+    for i in range(k):
+        own = (i + 1) * m // k - i * m // k
+        assert own >= 1 and abs(own - m / k) < 1
+        rows = orc.shard_indices(12345, i, k, 0, own, m)
+        assert rows.min() >= 0 and rows.max() < m and np.unique(rows).size == own
+        again = orc.shard_indices(12345, i, k, own, min(own, 50), m)      # a second pass repeats the order
+        assert np.array_equal(again, rows[:again.size])
+        assert np.array_equal(orc.shard_indices(12345, i, k, 3, 5, m), np.resize(rows, 8)[3:8])
+        seen.append(rows)
+    allrows = np.concatenate(seen)
+    assert np.array_equal(np.sort(allrows), np.arange(m))
+
+
+def test_shard_order_is_shuffled_and_depends_on_the_seed():
+    m, k = 10007, 4
+    a = orc.shard_indices(1, 0, k, 0, 2000, m)
+    b = orc.shard_indices(2, 0, k, 0, 2000, m)
+    assert not np.array_equal(a, b)
+    # not the identity, not sorted, and spread over the whole range: the mean rank of a node's rows is m/2
+    assert (np.diff(a) > 0).mean() == pytest.approx(0.5, abs=0.05)
+    assert a.mean() == pytest.approx(m / 2, rel=0.05) and b.mean() == pytest.approx(m / 2, rel=0.05)
+    # which node a row lands on is balanced over seeds: row 0 visits every node
+    owners = set()
+    for seed in range(40):
+        for i in range(k):
+            if 0 in orc.shard_indices(seed, i, k, 0, (i + 1) * m // k - i * m // k, m):
+                owners.add(i)
+    assert owners == set(range(k))
+
+
+def test_shard_sampling_rejects_bad_arguments():
+    for args in [(0, 0, 3, 0, 1, 2), (0, 3, 3, 0, 1, 10), (0, -1, 3, 0, 1, 10), (0, 0, 0, 0, 1, 10), (0, 0, 1, 0, 1, 0)]:
+        with pytest.raises(ValueError):
+            orc.shard_indices(*args)
+
+
 def test_index_streams_differ_by_chain_step_and_seed():
     a = orc.sample_indices(0, 0, 0, 64, 1 << 20)
     assert not np.array_equal(a, orc.sample_indices(0, 1, 0, 64, 1 << 20))
