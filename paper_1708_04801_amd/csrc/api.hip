@@ -166,11 +166,13 @@ static size_t state_elem_bytes(wpsgd_loss loss)
 }
 
 // workspace header: chain order, then (in that order) step counts, stream offsets, and three
-// 32-bit numbers per chain describing its share under partition-and-shuffle sampling
+// 32-bit numbers per chain describing its share under partition-and-shuffle sampling; last, the
+// powers (1-eta*lambda)^l and (1-eta*lambda)^-(l+1), l = 0..63, in fp64
+constexpr size_t kPowTabBytes = 2 * 64 * sizeof(double);
 static size_t header_bytes(int k)
 {
     return align256((size_t)k * sizeof(int32_t)) + 2 * align256((size_t)k * sizeof(int64_t)) +
-           align256((size_t)k * 3 * sizeof(uint32_t));
+           align256((size_t)k * 3 * sizeof(uint32_t)) + kPowTabBytes;
 }
 
 // Host arrays (chain order, step counts, weights) reach the device through a small ring of pinned
@@ -332,6 +334,17 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
         }
     }
 
+    double *pow_tab = reinterpret_cast<double *>(header.data() + header.size() - kPowTabBytes);
+    {
+        const double rho = 1.0 - eta * lambda, inv_rho = 1.0 / rho;
+        double up = 1.0, down = inv_rho;
+        for (int l = 0; l < 64; ++l) {
+            pow_tab[l] = up;
+            pow_tab[64 + l] = down;
+            up *= rho;
+            down *= inv_rho;
+        }
+    }
     char *ws = static_cast<char *>(workspace);
     int32_t *order_dev = reinterpret_cast<int32_t *>(ws);
     int64_t *steps_dev = reinterpret_cast<int64_t *>(ws + order_bytes);
@@ -355,6 +368,7 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     a.nsteps = steps_dev;
     a.step0 = offsets_dev;
     a.w_start = w_start;
+    a.pow_tab = reinterpret_cast<const double *>(ws + header_bytes(k) - kPowTabBytes);
     a.eta = eta;
     a.rho = 1.0 - eta * lambda;
     a.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);

@@ -504,24 +504,23 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
     if (n > 0) {
         const uint32_t off0 = (uint32_t)(tid * 16);                           // chunk c adds c*NT*16 bytes
         constexpr uint32_t kChunkStride = (uint32_t)(NT * 16);
-        const double rho = a.rho, inv_rho = 1.0 / a.rho;
-        double rho_pow = 1.0, inv_rho_pow1 = inv_rho, rho64 = rho, inv_rho64 = inv_rho;
-#pragma unroll
-        for (int bit = 0; bit < 6; ++bit) {
-            if ((lane >> bit) & 1) {
-                rho_pow *= rho64;
-                inv_rho_pow1 *= inv_rho64;
-            }
-            rho64 *= rho64;
-            inv_rho64 *= inv_rho64;
-        }
+        // Registers are what this kernel runs out of, so nothing that is only needed once per
+        // window of 64 steps stays in one: (1-eta*lambda)^lane and its inverse are read from a
+        // small table at every window start, and the next window's rows are computed when the
+        // look-ahead first reaches into it.
+        const double rho = a.rho;
+        const double rho64 = a.pow_tab[kWave - 1] * rho, inv_rho64 = a.pow_tab[2 * kWave - 1];
+        auto lane_powers = [&](double &rho_pow, double &inv_rho_pow1) {
+            rho_pow = a.pow_tab[lane];
+            inv_rho_pow1 = a.pow_tab[kWave + lane];
+        };
         double s_w = 1.0, eos_w = a.eta;
         const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
         // out of line: the registers are full of model and row here, and this runs once per 64 steps
         auto window_rows = [&](int64_t w) {
             return sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32, a.perm, (uint32_t)a.k);
         };
-        uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
+        uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window; the next (valid from position 62 on)
         TV zs_tab = (TV)0, cs_tab = (TV)0;     // per lane, label folded in: y*s_l (*log2 e), y*eta/s_{l+1}
         int parity = 0;
         Frag xr;                               // the row of the current step
@@ -587,8 +586,9 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
                         eos_w = a.eta;
                     }
                     rows_a = rows_b;
-                    rows_b = window_rows(step / kWave + 1);
                 }
+                double rho_pow, inv_rho_pow1;
+                lane_powers(rho_pow, inv_rho_pow1);
                 const double yl = (double)a.y[rows_a];
                 const double sl = s_w * rho_pow * yl, el = eos_w * inv_rho_pow1 * yl;
                 if constexpr (LOSS == kLossHinge) {
@@ -600,10 +600,10 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
                 }
             }
 
-            TV acc[4] = {(TV)0, (TV)0, (TV)0, (TV)0};
+            TV acc[2] = {(TV)0, (TV)0};         // two partial sums: registers are scarce here
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) acc[e & 3] += v[e] * (TV)xr.at(e);
-            TV tot = wave_sum_lane63((acc[0] + acc[1]) + (acc[2] + acc[3]));
+            for (int e = 0; e < EPT; ++e) acc[e & 1] += v[e] * (TV)xr.at(e);
+            TV tot = wave_sum_lane63(acc[0] + acc[1]);
             if (lane == kWave - 1) red[parity][wave] = tot;
             const TV zy = lane_read(zs_tab, j), cy = lane_read(cs_tab, j);
             __syncthreads();
@@ -627,6 +627,7 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
             }
 
             // row(step+1): LDS -> registers; row(step+2): HBM -> the slots just read
+            if (j == kWave - 2 && step > 0) rows_b = window_rows(step / kWave + 1);    // the look-ahead enters the next window
             const u32x4 r2 = row_at(j + 2);
 #pragma unroll
             for (int cidx = 0; cidx < CHUNKS; ++cidx) {
@@ -640,6 +641,8 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
 
         const int64_t last_w = (n - 1) / kWave;
         const int rem = (int)(n - last_w * kWave);
+        double rho_pow, inv_rho_pow1;
+        lane_powers(rho_pow, inv_rho_pow1);
         const double s_end = s_w * lane_read(rho_pow, rem - 1) * rho;
 #pragma unroll
         for (int e = 0; e < EPT; ++e) v[e] = (TV)(s_end * (double)v[e]);

@@ -26,6 +26,7 @@ struct ChainArgs {
     const int32_t *order;     // DEVICE, k entries: chain id run by workgroup b
     const int64_t *nsteps;    // DEVICE, k entries: steps of that chain
     const int64_t *step0;     // DEVICE, k entries: position in that chain's sample stream of its first step
+    const double *pow_tab;    // DEVICE, 128 entries: (1-eta*lambda)^l for l = 0..63, then (1-eta*lambda)^-(l+1)
     const float *w_start;     // DEVICE, d entries: every chain starts from this vector; NULL: from zero
     const uint32_t *perm;     // DEVICE, m entries: shuffled row order for partition-and-shuffle sampling;
                               // NULL: the with-replacement stream
