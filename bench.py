@@ -154,12 +154,16 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "chain kernel (wpsgd_run_chains)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "bytes_per_sample_update": bytes_per_update,
-                     "kernel_ms": chain_ms, "combine_ms": combine_ms},
+                     "kernel_ms": chain_ms, "combine_ms": combine_ms,
+                     # a chain is sequential: the launch lasts as long as its longest chain, so this
+                     # per-step time (not the memory system) is what sets the achieved bandwidth
+                     "longest_chain_steps": int(w.n_steps.max()),
+                     "us_per_step_longest_chain": chain_ms * 1e3 / max(1, int(w.n_steps.max()))},
         "data_generation_s": t_gen,
     }
 
-    # What one workgroup per chain can reach at all: k workgroups streaming rows of this size
-    # with no arithmetic, times the share of that time the chains are alive.
+    # What the memory side allows with one workgroup per chain: k workgroups streaming rows of
+    # this size with no arithmetic, times the share of that time the chains are alive.
     if not w.is_csr and w.row_bytes() >= 4096 and w.row_bytes() % 16 == 0:
         rows = int(min(w.n_steps.max(), 4096))
         best = None

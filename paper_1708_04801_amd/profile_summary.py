@@ -119,9 +119,12 @@ def main():
             "",
             f"Streaming ceiling of this mapping (`stream_rows_kernel`, {ceil['workgroups']} workgroups, no arithmetic): "
             f"{ceil['streaming_GBps']:.1f} GB/s; chains are alive {100 * ceil['alive_fraction']:.1f} % of the kernel's "
-            f"duration on average, so {ceil['attainable_GBps']:.1f} GB/s is attainable; the chain kernel reaches "
+            f"duration on average, so the memory side allows {ceil['attainable_GBps']:.1f} GB/s; the chain kernel reaches "
             f"{100 * ceil['frac_of_attainable']:.1f} % of that.",
         ]
+    if "us_per_step_longest_chain" in roof:
+        lines += ["", f"Longest chain: {roof['longest_chain_steps']} steps, {roof['us_per_step_longest_chain']:.3f} us per step "
+                      "(the launch lasts as long as its longest chain)."]
     lines.append(f"\nKernel source digest: {kernel_source_digest()}")
     os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
     with open(os.path.join(ROOT, "profiles", f"{short}_{workload}.md"), "w") as fh:
