@@ -191,6 +191,24 @@ __device__ inline T wave_sum_lane63(T v)
     return v;
 }
 
+// fp32: the two cross-row steps as single fused instructions (the masked rows keep their value,
+// so no zero has to be moved in first).  The same additions in the same order as above.  A DPP
+// operand written by the preceding VALU instruction needs two wait states.
+template <>
+__device__ inline float wave_sum_lane63<float>(float v)
+{
+    v += dpp_move<0xB1, 0xF>(v);
+    v += dpp_move<0x4E, 0xF>(v);
+    v += dpp_move<0x141, 0xF>(v);
+    v += dpp_move<0x140, 0xF>(v);
+    asm volatile("s_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "s_nop 1\n\t"
+                 "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf"
+                 : "+v"(v));
+    return v;
+}
+
 __device__ inline float read_lane63(float v)
 {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), kWave - 1));
