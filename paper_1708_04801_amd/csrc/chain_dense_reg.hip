@@ -98,6 +98,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     constexpr int D = B * P;                       // steps per group of P rounds
     static_assert(kWave % D == 0, "a 64-step window must hold whole groups");
     __shared__ TV red[2][NR][NW];
+    // Labels of a whole window, gathered straight into LDS one window ahead (per wave, two windows)
+    __shared__ float ylab[NW][2][kWave];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -122,7 +124,6 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 #pragma unroll
         for (int c = 0; c < Frag::kChunks; ++c) off[c] = (uint32_t)(((c * NT + tid) * VEC) * sizeof(TX));
         Frag x[P][B];
-        float yv[P][B];
 
         // (1-eta*lambda)^lane and (1-eta*lambda)^-(lane+1), by binary powering in fp64
         const double rho = a.rho, inv_rho = 1.0 / a.rho;
@@ -176,11 +177,23 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (int64_t)row * row_stride, row_bytes);
 #pragma unroll
                 for (int c = 0; c < Frag::kChunks; ++c) x[u][b].load_chunk(c, rx, off[c]);
-                // the label rides the same queue (a scalar load would be drained at every LDS wait)
-                const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y + row, 4u);
-                yv[u][b] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(ry, 0, 0, 0));
             }
         };
+        // Labels: the 64 labels of a window are gathered with one load per wave that lands in LDS
+        // (each lane's dword at slot + 4*lane), a whole window before they are read.  The compiler
+        // does not see that load, and nothing waits for it: memory operations of a wave complete
+        // in order and at most 63 can be outstanding, so after the hundreds of row loads of one
+        // window it has landed.  (A scalar load would be drained at every LDS wait, a per-step
+        // vector load costs a descriptor and an instruction per step.)
+        typedef __attribute__((address_space(3))) float *lds_fptr;
+        const uint32_t ylab_base = (uint32_t)(size_t)(lds_fptr)&ylab[0][0][0] + (uint32_t)wave * (2 * kWave * 4);
+        auto request_labels = [&](int64_t w, uint32_t rows) {
+            const float *py = a.y + rows;
+            const uint32_t slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ylab_base + (uint32_t)(w & 1) * (kWave * 4)));
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" : : "s"(slot), "v"(py) : "memory", "m0");
+        };
+        request_labels(0, rows_a);
+        request_labels(1, rows_b);
 
         int parity = 0;
         // One round: steps at in-window positions j .. j+B-1, rows in slot u.  While the partial
@@ -224,8 +237,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             TV zy[B], cy[B];
 #pragma unroll
             for (int b = 0; b < B; ++b) {
-                zy[b] = lane_read(zs_tab, j + b) * (TV)yv[u][b];
-                cy[b] = lane_read(cs_tab, j + b) * (TV)yv[u][b];
+                zy[b] = lane_read(zs_tab, j + b);
+                cy[b] = lane_read(cs_tab, j + b);
             }
             if constexpr (NW > 1) {
                 __syncthreads();
@@ -297,8 +310,10 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     }
                     rows_a = rows_b;
                     rows_b = window_rows(w + 1);
+                    request_labels(w + 1, rows_b);
                 }
-                const double sl = s_w * rho_pow, el = eos_w * inv_rho_pow1;
+                const double yl = (double)ylab[wave][w & 1][lane];      // requested a window ago (or before the loop)
+                const double sl = s_w * rho_pow * yl, el = eos_w * inv_rho_pow1 * yl;
                 const bool live = w * kWave + lane < n;
                 if constexpr (LOSS == kLossHinge) {
                     zs_tab = sl;
@@ -313,6 +328,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 round(u, j0 + u * B, (u + P - 1) % P, j0 + (u + P - 1) * B);
             j0 = (j0 + D) & (kWave - 1);
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // no label load may still be on its way to LDS when the wave ends
         // scale at the chain's end: s_w covers the steps before the last window
         const int64_t last_w = (n - 1) / kWave;
         const int rem = (int)(n - last_w * kWave);                          // 1..64 steps in it
