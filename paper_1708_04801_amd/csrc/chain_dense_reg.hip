@@ -167,17 +167,26 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 
         // Request the B rows (and labels) of the round at in-window position j (0 <= j < 128;
         // positions >= 64 lie in the next window) into slot u.
-        auto request = [&](int u, int j) {
+        auto describe = [&](int j, __amdgpu_buffer_rsrc_t (&rx)[B]) {
 #pragma unroll
             for (int b = 0; b < B; ++b) {
                 const int jj = j + b;
                 const uint32_t ra = (uint32_t)__builtin_amdgcn_readlane((int)rows_a, jj & (kWave - 1));
                 const uint32_t rb = (uint32_t)__builtin_amdgcn_readlane((int)rows_b, jj & (kWave - 1));
                 const uint32_t row = jj < kWave ? ra : rb;
-                const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (int64_t)row * row_stride, row_bytes);
-#pragma unroll
-                for (int c = 0; c < Frag::kChunks; ++c) x[u][b].load_chunk(c, rx, off[c]);
+                rx[b] = make_rsrc(X + (int64_t)row * row_stride, row_bytes);
             }
+        };
+        auto issue = [&](int u, const __amdgpu_buffer_rsrc_t (&rx)[B]) {
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+#pragma unroll
+                for (int c = 0; c < Frag::kChunks; ++c) x[u][b].load_chunk(c, rx[b], off[c]);
+        };
+        auto request = [&](int u, int j) {
+            __amdgpu_buffer_rsrc_t rx[B];
+            describe(j, rx);
+            issue(u, rx);
         };
         // Labels: the 64 labels of a window are gathered with one load per wave that lands in LDS
         // (each lane's dword at slot + 4*lane), a whole window before they are read.  The compiler
@@ -232,7 +241,10 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     for (int r = 0; r < NR; ++r) red[parity][r][wave] = tot[r];
                 }
             }
-            if constexpr (P > 1) request(u_prev, j_next);
+            // The next rows are described (scalar arithmetic) while the partial sums travel to LDS
+            // and requested while the workgroup's sums travel back: both waits hide something.
+            __amdgpu_buffer_rsrc_t next_rows[B];
+            if constexpr (P > 1) describe(j_next, next_rows);
             // per-step scalars with the label folded in, ready before the sums arrive
             TV zy[B], cy[B];
 #pragma unroll
@@ -242,15 +254,22 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             }
             if constexpr (NW > 1) {
                 __syncthreads();
+                TV part[NR][NW];
+#pragma unroll
+                for (int r = 0; r < NR; ++r)
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) part[r][w] = red[parity][r][w];
+                if constexpr (P > 1) issue(u_prev, next_rows);
 #pragma unroll
                 for (int r = 0; r < NR; ++r) {
-                    TV t = red[parity][r][0];
+                    TV t = part[r][0];
 #pragma unroll
-                    for (int w = 1; w < NW; ++w) t += red[parity][r][w];
+                    for (int w = 1; w < NW; ++w) t += part[r][w];
                     tot[r] = t;
                 }
                 parity ^= 1;
             } else {
+                if constexpr (P > 1) issue(u_prev, next_rows);
 #pragma unroll
                 for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
             }
