@@ -52,7 +52,7 @@ def main():
             stats.append(r)
     chain = next(r for r in stats if "chain_" in r["Name"])
     kernel_name = chain["Name"]
-    short = kernel_name.split("wpsgd::")[1].split("<")[0].split("(")[0]
+    short = kernel_name.split("<")[0].split("::")[-1].split("(")[0].replace("void ", "").strip()
 
     bench_line = None
     with open(os.path.join(prof, "stats_stdout.log")) as fh:
