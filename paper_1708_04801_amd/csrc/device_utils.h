@@ -261,23 +261,6 @@ __device__ inline double loss_slope(double y, double yhat)
     }
 }
 
-// Coefficient of one step in the scaled representation w = s*v:  v <- v + c*x with
-//   c = -eta * dL/dyhat(y, s*dot) / s_next,   dot = v.x,   s_next = (1-eta*lambda)*s.
-// eta_over_s_next = eta / s_next is handed in so that it stays off the dependent path.
-// Hinge decides y*yhat < 1 in fp64.  Logistic is smooth in yhat, so it runs on the fp32
-// hardware exponential and reciprocal (about 1e-6 relative error in c).
-__device__ inline double step_coef_hinge(double y, double dot, double s, double eta_over_s_next)
-{
-    return (y * (s * dot) < 1.0) ? y * eta_over_s_next : 0.0;
-}
-
-__device__ inline float step_coef_logistic(float y, float dot, float s, float eta_over_s_next)
-{
-    const float z = y * (s * dot);
-    const float e = __expf(z);                        // inf for large z -> c = 0; 0 for z << 0
-    return (y * eta_over_s_next) * __builtin_amdgcn_rcpf(1.0f + e);
-}
-
 // Model-vector precision by loss: the hinge slope is discontinuous in yhat, so a rounding-size
 // error in w can flip a step and displace the chain by eta*|x|; its state and dot products are
 // carried in fp64.  The logistic slope is smooth and fp32 state is accurate to ~1e-6.
