@@ -149,8 +149,9 @@ struct RowWindow {
 //   0x141 row_half_mirror (7 - lane%8) 0x140 row_mirror (15 - lane%16)
 //   0x142 row_bcast15: lane 15 of each row to every lane of the next row
 //   0x143 row_bcast31: lane 31 to every lane of rows 2 and 3
-// After the four in-row steps all 16 lanes of a row hold the row sum; bcast15 into rows 1 and 3,
-// then bcast31 into rows 2 and 3, leaves the wave total in row 3, i.e. in lane 63.
+// After the four in-row steps all 16 lanes of a row hold the row sum; bcast15 adds each row's sum
+// to the next row, then bcast31 adds row 1's to rows 2 and 3: the wave total is in row 3, i.e. in
+// lane 63 (and only there).
 // ---------------------------------------------------------------------------------------------
 template <int CTRL, int ROW_MASK>
 __device__ inline int dpp_move_bits(int x)
@@ -186,8 +187,11 @@ __device__ inline T wave_sum_lane63(T v)
     v += dpp_move<0x4E, 0xF>(v);
     v += dpp_move<0x141, 0xF>(v);
     v += dpp_move<0x140, 0xF>(v);
-    v += dpp_move<0x142, 0xA>(v);
-    v += dpp_move<0x143, 0xC>(v);
+    // The cross-row steps run unmasked: lanes without a source lane receive 0, rows 1 and 2 end up
+    // with sums nobody reads, and row 3 - lane 63 - adds (r3 + r2) + (r1 + r0) as it should.  (Masked
+    // to the rows that matter, each step would first need a zero moved into the other rows.)
+    v += dpp_move<0x142, 0xF>(v);
+    v += dpp_move<0x143, 0xF>(v);
     return v;
 }
 
