@@ -80,7 +80,12 @@ typedef struct wpsgd_plan {
     int rows;            /* where a dense row waits between its dot product and its update:
                             1 registers, requested `prefetch` rounds ahead; 2 registers, with the next
                             row landing in LDS meanwhile (rows up to 128 KiB); 3 nowhere: the row is
-                            streamed twice (rows too long for 1 and 2)                               */
+                            streamed twice (rows too long for 1 and 2); 4 registers, copied from a ring of
+                            LDS slots that waves of their own fill from HBM (256 worker threads)       */
+    int helpers;         /* dense, 256 threads, k a multiple of 8: workgroups per chain that run ahead of
+                            it on otherwise idle compute units and pull its rows into the L2 cache the
+                            chain's compute unit shares.  0: choose (up to 3 when compute units are to
+                            spare and rows are long); -1: none; 1..3: that many, room permitting       */
 } wpsgd_plan;
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----

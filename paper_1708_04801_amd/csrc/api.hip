@@ -80,8 +80,8 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
     p.loss = (int)loss;
     p.dtype = X->dense ? (int)X->dtype : WPSGD_F32;
     const size_t state_elem = (loss == WPSGD_HINGE) ? sizeof(double) : sizeof(float);
-    const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0, 0};
-    if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0 || f.rows < 0 || f.rows > 3) return WPSGD_INVALID_ARG;
+    const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0, 0, 0};
+    if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0 || f.rows < 0 || f.rows > 4 || f.helpers < -1 || f.helpers > 3) return WPSGD_INVALID_ARG;
 
     if (!X->dense) {
         if (f.threads && f.threads != kWave && f.threads != 2 * kWave) return WPSGD_UNSUPPORTED;
@@ -165,14 +165,35 @@ static size_t state_elem_bytes(wpsgd_loss loss)
     return loss == WPSGD_HINGE ? sizeof(double) : sizeof(float);
 }
 
-// workspace header: chain order, then (in that order) step counts, stream offsets, and three
-// 32-bit numbers per chain describing its share under partition-and-shuffle sampling; last, the
-// powers (1-eta*lambda)^l and (1-eta*lambda)^-(l+1), l = 0..63, in fp64
+// workspace header: chain order, then (in that order) step counts, stream offsets, three 32-bit
+// numbers per chain describing its share under partition-and-shuffle sampling, and a progress
+// counter per chain (zero at launch) that helper workgroups watch; last, the powers
+// (1-eta*lambda)^l and (1-eta*lambda)^-(l+1), l = 0..63, in fp64
 constexpr size_t kPowTabBytes = 2 * 64 * sizeof(double);
 static size_t header_bytes(int k)
 {
     return align256((size_t)k * sizeof(int32_t)) + 2 * align256((size_t)k * sizeof(int64_t)) +
-           align256((size_t)k * 3 * sizeof(uint32_t)) + kPowTabBytes;
+           align256((size_t)k * 3 * sizeof(uint32_t)) + align256((size_t)k * sizeof(uint32_t)) + kPowTabBytes;
+}
+
+// Helper workgroups per chain for a resolved plan: only the 256-thread register kernels have
+// them, only when k is a multiple of 8 (workgroups b and b+k then share an XCD and its L2 cache),
+// and only on compute units no chain occupies.
+static int helpers_per_chain(const Plan &p, const wpsgd_matrix *X, int k, const wpsgd_plan *force)
+{
+    if (p.family != Family::DenseReg || p.threads != 256 || p.rows != 1 || k % 8 != 0) return 0;
+    const int asked = force ? force->helpers : 0;
+    if (asked < 0) return 0;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cus = n;
+    }
+    const int room = (cus - k) / k;
+    const int64_t row_bytes = X->d * (X->dtype == WPSGD_BF16 ? 2 : 4);
+    const int want = asked > 0 ? asked : (row_bytes >= 8192 ? 3 : 0);
+    return std::max(0, std::min(want, std::min(room, 3)));
 }
 
 // Host arrays (chain order, step counts, weights) reach the device through a small ring of pinned
@@ -264,13 +285,16 @@ int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     Plan p;
     rc = resolve_plan(X, loss, plan, &p);
     if (rc != WPSGD_OK) return rc;
-    static const char *const kRows[] = {"", " rows=registers", " rows=lds", " rows=twice"};
-    std::snprintf(buf, buf_bytes, "%s %s %s nt=%d ept=%d vec=%d B=%d P=%d state=%s%s",
+    static const char *const kRows[] = {"", " rows=registers", " rows=lds", " rows=twice", " rows=fed"};
+    char helped[32] = "";
+    const int hp = helpers_per_chain(p, X, k, plan);
+    if (hp > 0) std::snprintf(helped, sizeof(helped), " helpers=%d", hp);
+    std::snprintf(buf, buf_bytes, "%s %s %s nt=%d ept=%d vec=%d B=%d P=%d state=%s%s%s",
                   family_name(p.family), p.dtype == WPSGD_BF16 ? "bf16" : "f32",
                   p.loss == WPSGD_HINGE ? "hinge" : "logistic", p.threads, p.ept, p.vec,
                   p.block_steps, p.prefetch,
                   p.state_bytes_per_elem == 0 ? "registers" : (p.state_bytes_per_elem == 8 ? "hbm-f64" : "hbm-f32"),
-                  p.family == Family::DenseReg ? kRows[p.rows] : "");
+                  p.family == Family::DenseReg ? kRows[p.rows] : "", helped);
     return WPSGD_OK;
 }
 
@@ -369,6 +393,8 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     a.step0 = offsets_dev;
     a.w_start = w_start;
     a.pow_tab = reinterpret_cast<const double *>(ws + header_bytes(k) - kPowTabBytes);
+    a.progress = reinterpret_cast<uint32_t *>(ws + order_bytes + 2 * steps_bytes + align256((size_t)k * 3 * sizeof(uint32_t)));
+    a.helpers = helpers_per_chain(p, X, k, plan) * k;
     a.eta = eta;
     a.rho = 1.0 - eta * lambda;
     a.seed_lo = (uint32_t)(seed & 0xFFFFFFFFu);

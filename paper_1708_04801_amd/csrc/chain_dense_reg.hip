@@ -84,6 +84,73 @@ struct RowFrag {
     }
 };
 
+// A helper workgroup (one whose index is k or more) runs ahead of a chain and touches one dword
+// of every 128-byte line of the rows the chain will visit, so that they sit in the L2 cache of the
+// chain's XCD when the chain asks for them.  One compute unit draws some 55-60 GB/s from HBM however
+// many loads it keeps in flight, which for 16 KiB rows is no faster than a chain can consume them;
+// out of L2 it draws more than twice that.  Workgroups are handed to the XCDs in turn, so with k a
+// multiple of 8 helper k*q + b and chain workgroup b share an XCD; the q-th of a chain's Q helpers
+// takes the steps t with t mod Q = q.  The chain publishes how far it has come; a helper stays
+// between kLeadMin and kLeadMax steps ahead of that (far enough to beat the chain's own requests,
+// close enough that the lines are still cached when they are used) and gives up when the chain
+// does not move, so it ends whatever the chain does.  The touched data lands in a scratch corner
+// of LDS and is never read.
+constexpr int kLeadMin = 10, kLeadMax = 26;
+
+template <typename TX>
+__device__ inline void run_ahead_of_chain(const ChainArgs &a, uint32_t *lds_sink)
+{
+    if (threadIdx.x >= kWave) return;                    // one wave does it
+    const int lane = (int)threadIdx.x;
+    const int h = (int)blockIdx.x - a.k;
+    const int b = h % a.k, q = h / a.k, Q = a.helpers / a.k;
+    const int chain = a.order[b];
+    const int64_t n = a.nsteps[b];
+    const int64_t step0 = a.step0[b];
+    const char *X = static_cast<const char *>(a.dense);
+    const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
+    const uint32_t row_bytes = (uint32_t)(a.d * (int64_t)sizeof(TX));
+    const uint32_t *progress = a.progress + b;
+    const uint32_t voff = (uint32_t)(lane * 128);        // an instruction touches 64 lines: 8 KiB of a row
+    typedef __attribute__((address_space(3))) uint32_t *lds_ptr;
+    const uint32_t sink = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)(lds_ptr)lds_sink);
+    uint32_t seen = 0;                                   // steps the chain has completed, as last read
+    int64_t polls = n + (1 << 20);                       // every wait below draws on this
+    bool alive = true;
+    for (int64_t w0 = 0; w0 < n && alive; w0 += kWave) {
+        const uint32_t rows = sample_window(a.seed_lo, a.seed_hi, (uint32_t)chain, step0 + w0, (uint32_t)a.m, a.perm,
+                                            (uint32_t)a.k);
+        for (int j = (int)((q + Q - (int)(w0 % Q)) % Q); j < kWave && w0 + j < n; j += Q) {
+            const uint32_t t = (uint32_t)(w0 + j);
+            while ((int32_t)(t - seen) > kLeadMax && polls > 0) {
+                seen = __hip_atomic_load(progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                --polls;
+                if ((int32_t)(t - seen) > kLeadMax) __builtin_amdgcn_s_sleep(16);
+            }
+            if (polls <= 0) {
+                alive = false;
+                break;
+            }
+            if ((int32_t)(t - seen) < kLeadMin) continue;        // the chain has asked for this row itself by now
+            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)rows, j);
+            const uint64_t base = (uint64_t)(uintptr_t)X + (uint64_t)row * (uint64_t)row_stride;
+            u32x4 rx;
+            rx[0] = (uint32_t)base;
+            rx[1] = (uint32_t)(base >> 32) & 0xffffu;
+            rx[2] = row_bytes;
+            rx[3] = 0x00020000u;
+            for (uint32_t piece = 0; piece < row_bytes; piece += 64 * 128) {
+                asm volatile("s_nop 4\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                             :
+                             : "s"(sink), "v"(voff), "s"(rx), "s"(piece)
+                             : "memory", "m0");
+            }
+            asm volatile("s_waitcnt vmcnt(12)" : : : "memory");
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");          // nothing may still be landing when the wave ends
+}
+
 // TX and LOSS are template parameters (not just per-file constants) so that the four builds of
 // this file produce four distinct sets of kernel symbols.
 template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P>
@@ -101,6 +168,10 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     // Labels of a whole window, gathered straight into LDS one window ahead (per wave, two windows)
     __shared__ float ylab[NW][2][kWave];
 
+    if ((int)blockIdx.x >= a.k) {       // a helper workgroup: see run_ahead_of_chain
+        run_ahead_of_chain<TX>(a, reinterpret_cast<uint32_t *>(&ylab[0][0][0]));
+        return;
+    }
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
@@ -165,8 +236,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         uint32_t rows_a = window_rows(0), rows_b = window_rows(1);   // this window and the next
         TV zs_tab = (TV)0, cs_tab = (TV)0;   // per lane: s_l (times log2(e) for logistic), eta/s_{l+1}
 
-        // Request the B rows (and labels) of the round at in-window position j (0 <= j < 128;
-        // positions >= 64 lie in the next window) into slot u.
+        // Descriptors of the B rows of the round at in-window position j (0 <= j < 128; positions
+        // >= 64 lie in the next window), straight from the row numbers: used before the loop only.
         auto describe = [&](int j, __amdgpu_buffer_rsrc_t (&rx)[B]) {
 #pragma unroll
             for (int b = 0; b < B; ++b) {
@@ -175,6 +246,31 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 const uint32_t rb = (uint32_t)__builtin_amdgcn_readlane((int)rows_b, jj & (kWave - 1));
                 const uint32_t row = jj < kWave ? ra : rb;
                 rx[b] = make_rsrc(X + (int64_t)row * row_stride, row_bytes);
+            }
+        };
+        // Inside the loop a round requests the rows of the round kAhead steps later.  Their
+        // addresses are tabulated once per window, one step per lane: lane l holds the address of
+        // the row of step l + kAhead of the window (the upper lanes reach into the next window), so
+        // that a request costs two lane reads instead of a 64-bit multiply-add on the scalar unit.
+        constexpr int kAhead = (P == 1 ? 1 : P - 1) * B;
+        static_assert(kAhead < kWave, "the look-ahead stays within one window");
+        uint32_t req_lo = 0, req_hi = 0;
+        auto tabulate_requests = [&]() {
+            const int src = ((lane + kAhead) & (kWave - 1)) * 4;
+            const uint32_t ra = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)rows_a);
+            const uint32_t rb = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)rows_b);
+            const uint32_t row = lane + kAhead < kWave ? ra : rb;
+            const uint64_t base = (uint64_t)(uintptr_t)X + (uint64_t)row * (uint64_t)row_stride;
+            req_lo = (uint32_t)base;
+            req_hi = (uint32_t)(base >> 32);
+        };
+        // descriptors of the rows to request while the round at position j (0 <= j < 64) runs
+        auto describe_ahead = [&](int j, __amdgpu_buffer_rsrc_t (&rx)[B]) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const uint64_t lo = (uint32_t)__builtin_amdgcn_readlane((int)req_lo, j + b);
+                const uint64_t hi = (uint32_t)__builtin_amdgcn_readlane((int)req_hi, j + b);
+                rx[b] = make_rsrc(reinterpret_cast<const void *>((hi << 32) | lo), row_bytes);
             }
         };
         auto issue = [&](int u, const __amdgpu_buffer_rsrc_t (&rx)[B]) {
@@ -207,8 +303,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         int parity = 0;
         // One round: steps at in-window positions j .. j+B-1, rows in slot u.  While the partial
         // sums cross the workgroup, slot u_prev (consumed one round ago) is requested again for
-        // the round at position j_next.
-        auto round = [&](int u, int j, int u_prev, int j_next) {
+        // the round kAhead steps from here.
+        auto round = [&](int u, int j, int u_prev) {
             TV acc[NR][NACC];
 #pragma unroll
             for (int r = 0; r < NR; ++r)
@@ -244,7 +340,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             // The next rows are described (scalar arithmetic) while the partial sums travel to LDS
             // and requested while the workgroup's sums travel back: both waits hide something.
             __amdgpu_buffer_rsrc_t next_rows[B];
-            if constexpr (P > 1) describe(j_next, next_rows);
+            if constexpr (P > 1) describe_ahead(j, next_rows);
             // per-step scalars with the label folded in, ready before the sums arrive
             TV zy[B], cy[B];
 #pragma unroll
@@ -298,7 +394,11 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 #pragma unroll
                 for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
             }
-            if constexpr (P == 1) request(u, j + B);      // a single slot: refill once it is free
+            if constexpr (P == 1) {                       // a single slot: refill once it is free
+                __amdgpu_buffer_rsrc_t rx[B];
+                describe_ahead(j, rx);
+                issue(u, rx);
+            }
         };
 
         // Slots 0..P-2 hold rounds 0..P-2 on entry to the loop; round r refills the slot of
@@ -316,6 +416,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         const int64_t ngroups = (nblk + P - 1) / P;
         int j0 = 0;                                 // in-window position of the group's first step
         for (int64_t g = 0; g < ngroups; ++g) {
+            if (a.helpers > 0 && tid == 0) a.progress[blockIdx.x] = (uint32_t)(g * D);   // for the helpers to see
             if (j0 == 0) {      // a new window of 64 steps begins (never in the middle of a group)
                 const int64_t w = (g * D) / kWave;
                 if (w > 0) {
@@ -331,6 +432,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     rows_b = window_rows(w + 1);
                     request_labels(w + 1, rows_b);
                 }
+                tabulate_requests();
                 const double yl = (double)ylab[wave][w & 1][lane];      // requested a window ago (or before the loop)
                 const double sl = s_w * rho_pow * yl, el = eos_w * inv_rho_pow1 * yl;
                 const bool live = w * kWave + lane < n;
@@ -344,7 +446,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             }
 #pragma unroll
             for (int u = 0; u < P; ++u)
-                round(u, j0 + u * B, (u + P - 1) % P, j0 + (u + P - 1) * B);
+                round(u, j0 + u * B, (u + P - 1) % P);
             j0 = (j0 + D) & (kWave - 1);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);      // no label load may still be on its way to LDS when the wave ends
@@ -690,12 +792,364 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
     }
 }
 
+// Rows fed through LDS by waves of their own.  A wave that issues vector memory loads pays for
+// them in its own instruction stream (a 16 KiB row costs the four waves of a chain some 200 cycles
+// per step that nothing hides), while other waves of the same SIMD are not slowed down by those
+// loads at all.  So the workgroup is split: NT threads ("workers") hold the model vector and run
+// the recursion exactly as in the register kernel, and as many threads again ("movers") do nothing
+// but bring rows from HBM straight into a ring of LDS slots (loads that land in LDS need no
+// registers while in flight).  A worker copies the rows of the next round from the ring into
+// registers while the partial sums of the current round cross the workgroup.
+//
+// One barrier per round synchronises everything.  With rounds r = 0, 1, ... of B steps each and
+// a ring of R rows, barrier r separates
+//   workers: rows of round r read from the ring and consumed | rows of round r+1 read from the ring
+//   movers : rows of round r+1 have landed (loads complete in issue order, so "at most
+//            (R-2B) rows' worth outstanding" says so) | the slots of round r are refilled with
+//            the rows of the steps R ahead.
+template <typename TX, int LOSS, int NT, int EPT, int VEC, int B>
+__global__ __launch_bounds__(2 * NT) void chain_dense_fed_kernel(ChainArgs a)
+{
+    using TV = typename StateType<LOSS>::type;
+    using Frag = RowFrag<TX, NT, EPT, VEC>;
+    static_assert(VEC * sizeof(TX) == 16, "16-byte loads only");
+    constexpr int NW = NT / kWave;
+    constexpr int NG = B * (B - 1) / 2;
+    constexpr int NR = B + NG;
+    constexpr int NACC = EPT >= 4 ? 4 : EPT;
+    constexpr int CHUNKS = EPT / VEC;                       // 16-byte pieces of a row per worker = loads per mover wave and row
+    constexpr int kSlotBytes = NT * EPT * (int)sizeof(TX);  // a row, padded to what the workers span
+    constexpr int kRingMax = (144 * 1024) / kSlotBytes;
+    constexpr int R = ((kRingMax > 16 ? 16 : kRingMax) / B) * B;    // rows in the ring: a whole number of rounds
+    static_assert(R >= 4 * B, "the ring holds the round in use, the next two and one in flight");
+    static_assert((R - 2 * B) * CHUNKS <= 63, "the mover's waits must be encodable");
+    static_assert(kWave % (2 * B) == 0 && R < kWave, "windows hold whole pairs of rounds");
+    __shared__ __attribute__((aligned(16))) uint32_t ring[R * kSlotBytes / 4];
+    __shared__ TV red[2][NR][NW];
+    __shared__ float ylab[NW][2][kWave];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const bool mover = wave_all >= NW;
+    const int wave = mover ? wave_all - NW : wave_all;
+    const int wtid = tid & (NT - 1);                        // index among the workers (or among the movers)
+    const int chain = a.order[blockIdx.x];
+    const int64_t n = a.nsteps[blockIdx.x];
+    const char *X = static_cast<const char *>(a.dense);
+    const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
+    const uint32_t row_bytes = (uint32_t)(a.d * (int64_t)sizeof(TX));
+    float *out = a.W + (int64_t)chain * a.d;
+    const int64_t step0 = a.step0[blockIdx.x];
+
+    // Columns past d are never loaded (the loads stop at the end of the row), so their ring bytes
+    // keep the zeros written here and contribute nothing.
+    for (int i = tid * 4; i < R * kSlotBytes / 4; i += 2 * NT * 4) {
+        ring[i + 0] = 0u;
+        ring[i + 1] = 0u;
+        ring[i + 2] = 0u;
+        ring[i + 3] = 0u;
+    }
+    __syncthreads();
+
+    TV v[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) v[e] = (TV)0;
+
+    // rounds both kinds of wave run: whole pairs (the workers alternate between two register sets)
+    const int64_t nblk = (n + B - 1) / B;
+    const int64_t npairs = (nblk + 1) / 2;
+
+    const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
+    uint32_t shard_lo = 0, shard_len = 1, shard_inc = 0, shard_pos = 0;
+    if (a.perm) {
+        shard_lo = a.shard[blockIdx.x];
+        shard_len = a.shard[a.k + blockIdx.x];
+        const uint32_t pos0 = a.shard[2 * a.k + blockIdx.x], room = shard_len - pos0;
+        shard_inc = (uint32_t)kWave % shard_len;
+        shard_pos = (uint32_t)lane < room ? pos0 + (uint32_t)lane : ((uint32_t)lane - room) % shard_len;
+    }
+    // rows visited in window w, one step per lane; windows are asked for in order 0, 1, 2, ...
+    auto window_rows = [&](int64_t w) {
+        if (a.perm) {
+            const uint32_t *p = a.perm + ((uint64_t)shard_lo + shard_pos);
+            uint32_t r;
+            asm volatile("global_load_dword %0, %1, off\n\ts_waitcnt vmcnt(0)" : "=v"(r) : "v"(p) : "memory");
+            const uint32_t t = shard_pos + shard_inc;
+            shard_pos = (t < shard_pos || t >= shard_len) ? t - shard_len : t;
+            return r;
+        }
+        return sample_row(seed_lo, seed_hi, (uint32_t)chain, (uint64_t)(step0 + w * kWave + lane), m32);
+    };
+    typedef __attribute__((address_space(3))) uint32_t *lds_ptr;
+    const uint32_t ring_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)(lds_ptr)&ring[0]);
+
+    if (n > 0 && mover) {
+        uint32_t rows_a = window_rows(0), rows_b = window_rows(1);
+        // lane l: address of the row of step l + R of the window
+        uint32_t req_lo = 0, req_hi = 0;
+        auto tabulate_requests = [&]() {
+            const int src = ((lane + R) & (kWave - 1)) * 4;
+            const uint32_t ra = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)rows_a);
+            const uint32_t rb = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)rows_b);
+            const uint32_t row = lane + R < kWave ? ra : rb;
+            const uint64_t base = (uint64_t)(uintptr_t)X + (uint64_t)row * (uint64_t)row_stride;
+            req_lo = (uint32_t)base;
+            req_hi = (uint32_t)(base >> 32) & 0xffffu;
+        };
+        const uint32_t voff = (uint32_t)(lane * 16);
+        // this wave's share of the row at `base` (16 bits of stride field zero, reads past the end
+        // dropped) into the ring slot at byte position `pos`
+        auto fetch = [&](uint32_t lo, uint32_t hi, uint32_t pos) {
+            u32x4 rx;
+            rx[0] = lo;
+            rx[1] = hi;
+            rx[2] = row_bytes;
+            rx[3] = 0x00020000u;
+#pragma unroll
+            for (int q = 0; q < CHUNKS; ++q) {
+                const uint32_t piece = (uint32_t)((q * NW + wave) * (kWave * 16));
+                // (the descriptor words may come straight from lane reads: leave the scalar
+                // registers time to settle before a memory instruction reads them)
+                asm volatile("s_nop 4\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                             :
+                             : "s"(ring_base + pos + piece), "v"(voff), "s"(rx), "s"(piece)
+                             : "memory", "m0");
+            }
+        };
+        // the whole ring first: rows 0 .. R-1
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane((int)rows_a, r);
+            const uint64_t base = (uint64_t)(uintptr_t)X + (uint64_t)row * (uint64_t)row_stride;
+            fetch((uint32_t)base, (uint32_t)(base >> 32) & 0xffffu, (uint32_t)(r * kSlotBytes));
+        }
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((R - 2 * B) * CHUNKS) : "memory");     // rounds 0 and 1 have landed
+        __syncthreads();
+        uint32_t pos = 0;                           // ring position of the round whose slots are refilled next
+        int j = 0;                                  // its in-window position
+        for (int64_t r = 0; r < 2 * npairs; ++r) {
+            if (j == 0) {
+                const int64_t w = (r * B) / kWave;
+                if (w > 0) {
+                    rows_a = rows_b;
+                    rows_b = window_rows(w + 1);
+                }
+                tabulate_requests();
+            }
+            asm volatile("s_waitcnt vmcnt(%0)" : : "n"((R - 3 * B) * CHUNKS) : "memory");  // round r+2 has landed
+            __syncthreads();
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)req_lo, j + b);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)req_hi, j + b);
+                fetch(lo, hi, pos + (uint32_t)(b * kSlotBytes));
+            }
+            pos += (uint32_t)(B * kSlotBytes);
+            if (pos == (uint32_t)(R * kSlotBytes)) pos = 0;
+            j = (j + B) & (kWave - 1);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" : : : "memory");      // nothing may still be landing when the wave ends
+        return;
+    }
+    if (mover) return;
+
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int64_t col = ((int64_t)(e / VEC) * NT + wtid) * VEC + (e % VEC);
+        v[e] = (a.w_start && col < a.d) ? (TV)a.w_start[col] : (TV)0;
+    }
+
+    if (n > 0) {
+        Frag x[2][B];
+        const double rho = a.rho, inv_rho = 1.0 / a.rho;
+        double rho_pow = 1.0, inv_rho_pow1 = inv_rho, rho64 = rho, inv_rho64 = inv_rho;
+#pragma unroll
+        for (int bit = 0; bit < 6; ++bit) {
+            if ((lane >> bit) & 1) {
+                rho_pow *= rho64;
+                inv_rho_pow1 *= inv_rho64;
+            }
+            rho64 *= rho64;
+            inv_rho64 *= inv_rho64;
+        }
+        double s_w = 1.0, eos_w = a.eta;
+        uint32_t rows_b = 0;
+        TV zs_tab = (TV)0, cs_tab = (TV)0;
+
+        // labels of a window: one gather per wave that lands in LDS, asked for a window ahead
+        typedef __attribute__((address_space(3))) float *lds_fptr;
+        const uint32_t ylab_base = (uint32_t)(size_t)(lds_fptr)&ylab[0][0][0] + (uint32_t)wave * (2 * kWave * 4);
+        auto request_labels = [&](int64_t w, uint32_t rows) {
+            const float *py = a.y + rows;
+            const uint32_t slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ylab_base + (uint32_t)(w & 1) * (kWave * 4)));
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" : : "s"(slot), "v"(py) : "memory", "m0");
+        };
+        request_labels(0, window_rows(0));
+        rows_b = window_rows(1);
+        request_labels(1, rows_b);
+
+        // rows of a round from the ring (byte position pos) into register set u
+        const uint32_t my_off = (uint32_t)(wtid * 16);
+        auto take = [&](int u, uint32_t pos) {
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+#pragma unroll
+                for (int c = 0; c < CHUNKS; ++c) {
+                    const u32x4 q = *reinterpret_cast<const u32x4 *>(
+                        reinterpret_cast<const char *>(ring) + (pos + my_off) + (b * kSlotBytes + c * NT * 16));
+                    x[u][b].w[4 * c + 0] = q[0];
+                    x[u][b].w[4 * c + 1] = q[1];
+                    x[u][b].w[4 * c + 2] = q[2];
+                    x[u][b].w[4 * c + 3] = q[3];
+                }
+        };
+
+        int parity = 0;
+        uint32_t pos_next = (uint32_t)(B * kSlotBytes);     // ring position of the round after the current one
+        auto round = [&](int u, int j) {
+            TV acc[NR][NACC];
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int q = 0; q < NACC; ++q) acc[r][q] = (TV)0;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                TV xe[B];
+#pragma unroll
+                for (int b = 0; b < B; ++b) xe[b] = (TV)x[u][b].at(e);
+#pragma unroll
+                for (int b = 0; b < B; ++b) acc[b][e % NACC] += v[e] * xe[b];
+                int g = B;
+#pragma unroll
+                for (int q = 0; q < B; ++q)
+#pragma unroll
+                    for (int b = q + 1; b < B; ++b) acc[g++][e % NACC] += xe[q] * xe[b];
+            }
+            TV tot[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                TV t = acc[r][0];
+#pragma unroll
+                for (int q = 1; q < NACC; ++q) t += acc[r][q];
+                tot[r] = wave_sum_lane63(t);
+            }
+            if (lane == kWave - 1) {
+#pragma unroll
+                for (int r = 0; r < NR; ++r) red[parity][r][wave] = tot[r];
+            }
+            // The rows of the next round move from the ring to registers while this wave waits at
+            // the barrier: a wave cannot issue while data returns into its registers, and here it
+            // has nothing to issue anyway.  LDS operations of a wave complete in order, so once
+            // at most the B*CHUNKS reads are outstanding the partial sums above are in LDS.
+            asm volatile("" : : : "memory");
+            take(u ^ 1, pos_next);
+            pos_next += (uint32_t)(B * kSlotBytes);
+            if (pos_next == (uint32_t)(R * kSlotBytes)) pos_next = 0;
+            TV zy[B], cy[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                zy[b] = lane_read(zs_tab, j + b);
+                cy[b] = lane_read(cs_tab, j + b);
+            }
+            asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(B * CHUNKS) : "memory");
+            __builtin_amdgcn_s_barrier();
+            TV part[NR][NW];
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int w = 0; w < NW; ++w) part[r][w] = red[parity][r][w];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                TV t = part[r][0];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) t += part[r][w];
+                tot[r] = t;
+            }
+            parity ^= 1;
+            TV c[B];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                TV dot = tot[b];
+                int g = B;
+#pragma unroll
+                for (int q = 0; q < B; ++q)
+#pragma unroll
+                    for (int bb = q + 1; bb < B; ++bb) {
+                        if (bb == b) dot += c[q] * tot[g];
+                        ++g;
+                    }
+                if constexpr (LOSS == kLossHinge) {
+                    c[b] = (zy[b] * dot < 1.0) ? cy[b] : 0.0;
+                } else {
+                    c[b] = cy[b] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(zy[b] * dot));
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+#pragma unroll
+                for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
+            }
+        };
+
+        __syncthreads();            // round 0 has landed in the ring
+        take(0, 0u);
+
+        int j0 = 0;
+        for (int64_t g = 0; g < npairs; ++g) {
+            if (j0 == 0) {      // a new window of 64 steps begins
+                const int64_t w = (g * 2 * B) / kWave;
+                if (w > 0) {
+                    s_w *= rho64;
+                    eos_w *= inv_rho64;
+                    if (s_w < 0x1p-30) {
+#pragma unroll
+                        for (int e = 0; e < EPT; ++e) v[e] *= (TV)s_w;
+                        s_w = 1.0;
+                        eos_w = a.eta;
+                    }
+                    rows_b = window_rows(w + 1);
+                }
+                // the labels of this window were asked for a window ago; the workers issue no
+                // other vector memory operation, so the queue is simply drained here
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                if (w > 0) request_labels(w + 1, rows_b);
+                const double yl = (double)ylab[wave][w & 1][lane];
+                const double sl = s_w * rho_pow * yl, el = eos_w * inv_rho_pow1 * yl;
+                const bool live = w * kWave + lane < n;
+                if constexpr (LOSS == kLossHinge) {
+                    zs_tab = sl;
+                    cs_tab = live ? el : 0.0;
+                } else {
+                    zs_tab = (float)(sl * 1.4426950408889634);
+                    cs_tab = live ? (float)el : 0.0f;
+                }
+            }
+            round(0, j0);
+            round(1, j0 + B);
+            j0 = (j0 + 2 * B) & (kWave - 1);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        const int64_t last_w = (n - 1) / kWave;
+        const int rem = (int)(n - last_w * kWave);
+        const double s_end = s_w * lane_read(rho_pow, rem - 1) * rho;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) v[e] = (TV)(s_end * (double)v[e]);
+    }
+
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int64_t col = ((int64_t)(e / VEC) * NT + wtid) * VEC + (e % VEC);
+        if (col < a.d) out[col] = (float)v[e];
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Instantiated variants: V(threads, elements per thread, load width, B, P).  Within one
 // (threads, ept, vec) shape the first entry is the default; the others are reachable through a
 // forced plan.  Register budget per thread: 512 at 256 threads, 256 at 512, 128 at 1024.
 // P > 0: rows wait in registers, P rounds requested ahead.  P = -1: the next row is staged in LDS.
-// P = 0: rows are streamed twice.
+// P = 0: rows are streamed twice.  P = -2: rows are fed through an LDS ring by mover waves.
 // ---------------------------------------------------------------------------------------------
 // 64 elements per thread only with fp32 state (logistic): 64 fp64 values would fill the registers
 #if WPSGD_LOSS == 1
@@ -718,15 +1172,19 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
     V(64, 8, 8, 1, 8) V(64, 8, 8, 4, 2)                                                        \
     V(256, 8, 8, 1, 8) V(256, 16, 8, 1, 8) V(256, 32, 8, 1, 4) V(256, 32, 8, 4, 2)             \
     V(256, 8, 8, 4, 2) V(256, 16, 8, 4, 2)                                                     \
+    V(256, 8, 8, 1, -2) V(256, 16, 8, 1, -2) V(256, 32, 8, 1, -2)                              \
+    V(256, 8, 8, 2, -2) V(256, 16, 8, 2, -2) V(256, 32, 8, 2, -2)                              \
     V(1024, 16, 8, 1, -1) V(1024, 32, 8, 1, -1) WPSGD_WIDEST_LDS(V, 8)                          \
     V(1024, 16, 8, 1, 0) V(1024, 32, 8, 1, 0) WPSGD_WIDEST(V, 8)
 #define WPSGD_VARIANTS_WIDE(V)
 #else
 #define WPSGD_VARIANTS_VEC(V)                                                                  \
     V(64, 4, 4, 1, 8) V(64, 4, 4, 1, 16) V(64, 4, 4, 2, 4) V(64, 4, 4, 4, 2)                   \
-    V(256, 4, 4, 1, 8) V(256, 8, 4, 1, 8) V(256, 16, 4, 1, 8) V(256, 32, 4, 1, 4)              \
+    V(256, 4, 4, 1, 8) V(256, 8, 4, 1, 8) V(256, 16, 4, 1, 8) V(256, 32, 4, 1, 4) V(256, 16, 4, 1, 16) V(256, 8, 4, 1, 16)             \
     V(256, 4, 4, 4, 2) V(256, 8, 4, 4, 2) V(256, 16, 4, 4, 2) V(256, 16, 4, 1, 4)              \
     V(256, 16, 4, 2, 2) V(256, 16, 4, 2, 4) V(256, 16, 4, 2, 8) V(256, 32, 4, 4, 2)            \
+    V(256, 4, 4, 1, -2) V(256, 8, 4, 1, -2) V(256, 16, 4, 1, -2) V(256, 32, 4, 1, -2)          \
+    V(256, 4, 4, 2, -2) V(256, 8, 4, 2, -2) V(256, 16, 4, 2, -2)                               \
     V(512, 8, 4, 1, 8) V(512, 8, 4, 4, 2) V(512, 8, 4, 2, 4)                                   \
     V(1024, 4, 4, 1, 8) V(1024, 4, 4, 4, 2) V(1024, 4, 4, 2, 4)                                \
     V(1024, 16, 4, 1, -1) V(1024, 32, 4, 1, -1)                                                \
@@ -739,12 +1197,28 @@ __global__ __launch_bounds__(NT) void chain_dense_lds_kernel(ChainArgs a)
 template <int NT, int EPT, int VEC, int BB, int PP>
 static void launch_variant(const ChainArgs &a, hipStream_t s)
 {
-    if constexpr (PP < 0) {
+    if constexpr (PP == -2) {
+        hipLaunchKernelGGL((chain_dense_fed_kernel<RowElem, kLoss, NT, EPT, VEC, BB>), dim3(a.k), dim3(2 * NT), 0, s, a);
+    } else if constexpr (PP < 0) {
         hipLaunchKernelGGL((chain_dense_lds_kernel<RowElem, kLoss, NT, EPT, VEC>), dim3(a.k), dim3(NT), 0, s, a);
     } else if constexpr (PP == 0) {
         hipLaunchKernelGGL((chain_dense_wide_kernel<RowElem, kLoss, NT, EPT, VEC>), dim3(a.k), dim3(NT), 0, s, a);
     } else {
-        hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP>), dim3(a.k), dim3(NT), 0, s, a);
+        auto kernel = chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP>;
+        size_t claim = 0;
+        if (a.helpers > 0) {
+            // more than half of a compute unit's LDS per workgroup: chains and helpers each get a unit of their own
+            static int allowed = 0;         // 0 not asked yet, 1 granted, -1 refused
+            if (allowed == 0) {
+                allowed = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, 84 * 1024) == hipSuccess ? 1 : -1;
+                if (allowed < 0) (void)hipGetLastError();
+            }
+            if (allowed > 0) claim = 84 * 1024;
+        }
+        ChainArgs b = a;
+        if (claim == 0) b.helpers = 0;
+        hipLaunchKernelGGL(kernel, dim3(b.k + b.helpers), dim3(NT), claim, s, b);
     }
 }
 
@@ -756,7 +1230,7 @@ static void launch_variant(const ChainArgs &a, hipStream_t s)
 #define WPSGD_SUFFIX WPSGD_CAT(f32_loss, WPSGD_LOSS)
 #endif
 
-constexpr int rows_kind(int pp) { return pp > 0 ? 1 : (pp < 0 ? 2 : 3); }
+constexpr int rows_kind(int pp) { return pp > 0 ? 1 : (pp == -1 ? 2 : (pp == 0 ? 3 : 4)); }
 
 // find(plan, launch?): walks the table; exact match on (threads, ept, vec, B, P, rows) where the
 // plan gives them, else the first entry of the shape.

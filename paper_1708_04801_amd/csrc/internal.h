@@ -35,6 +35,10 @@ struct ChainArgs {
     // hyper-parameters (fp64 on purpose: (1-eta*lambda)^n must not be compounded in fp32)
     double eta, rho;          // rho = 1 - eta*lambda
     uint32_t seed_lo, seed_hi;
+    // Helper workgroups (dense register kernels): workgroups k .. k+helpers-1 run ahead of the
+    // chains and pull their rows into the L2 cache; helpers is a multiple of k (or 0).
+    int helpers;
+    uint32_t *progress;       // DEVICE, k entries, zero at launch: steps workgroup b has completed (low 32 bits)
     // outputs / scratch
     float *W;                 // k x d
     void *state;              // k x d model vectors in HBM (state_in_hbm plans), else unused
@@ -52,7 +56,8 @@ struct Plan {
     int vec;         // elements per global load instruction
     int block_steps; // B
     int prefetch;    // P: rounds in flight
-    int rows;        // DenseReg: 1 rows wait in registers, 2 next row staged in LDS, 3 rows streamed twice
+    int rows;        // DenseReg: 1 rows wait in registers, 2 next row staged in LDS, 3 rows streamed twice,
+                     // 4 rows fed through an LDS ring by mover waves
     size_t state_bytes_per_elem;   // 0 when the state lives in registers
 };
 

@@ -133,6 +133,11 @@ DENSE_PLANS = [
     (12000, wl.LOGISTIC, {"rows": 3}), (16384, wl.HINGE, {"rows": 3}), (20000, wl.LOGISTIC, {"rows": 3}),
     (20000, wl.HINGE, {"rows": 2}), (32768, wl.LOGISTIC, {"rows": 2}), (32768, wl.HINGE, None),
     (40000, wl.LOGISTIC, None),
+    # rows brought in by mover waves through an LDS ring
+    (4096, wl.LOGISTIC, {"rows": 4}), (4096, wl.HINGE, {"rows": 4}), (4096, wl.LOGISTIC, {"rows": 4, "block_steps": 2}),
+    (4096, wl.HINGE, {"rows": 4, "block_steps": 2}), (1000, wl.LOGISTIC, {"rows": 4}), (3000, wl.HINGE, {"rows": 4}),
+    (2048, wl.LOGISTIC, {"rows": 4, "block_steps": 2}), (1500, wl.HINGE, {"rows": 4, "block_steps": 2}),
+    (8192, wl.HINGE, {"rows": 4}), (8000, wl.LOGISTIC, {"rows": 4}), (260, wl.LOGISTIC, {"rows": 4}),
 ]
 
 
@@ -148,7 +153,7 @@ def test_dense_fp32_chains(d, loss, plan):
     Xg = api.matrix_from_workload(w)
     desc = api.wpsgd_describe_plan(Xg, k, loss, plan)
     if plan and "rows" in plan:
-        assert ("rows=lds" if plan["rows"] == 2 else "rows=twice") in desc
+        assert {2: "rows=lds", 3: "rows=twice", 4: "rows=fed"}[plan["rows"]] in desc
     W = gpu_chains(w, plan=plan, X=Xg)
     check_against_oracle(w, W, label=f"d={d} [{desc}]")
     assert (W[2] == 0).all()                                     # idle chain keeps w_0 = 0
@@ -156,10 +161,33 @@ def test_dense_fp32_chains(d, loss, plan):
     assert torch.equal(W, W2)                                    # same inputs, same bits
 
 
+@pytest.mark.parametrize("k,d,helpers", [(8, 4096, 3), (16, 4096, 1), (8, 2048, 2), (24, 8192, 0), (8, 1000, 3)])
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_dense_chains_with_helper_workgroups(k, d, helpers, loss):
+    """Workgroups that run ahead of the chains and pull their rows into L2 change when a row arrives,
+    never what is computed: same bits as without them, and the oracle's result."""
+    rng = np.random.default_rng(k * 31 + d + loss)
+    m = 700
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = rng.integers(0, 400, size=k).astype(np.int64)
+    n[0], n[1] = 0, 1
+    w = wl.Workload("helped", loss, 0.3, 1e-3, 5, n, y, m, d, dense=X)
+    Xg = api.matrix_from_workload(w)
+    plan = {"threads": 256, "helpers": helpers}
+    desc = api.wpsgd_describe_plan(Xg, k, loss, plan)
+    assert (f"helpers={helpers}" if helpers else "helpers=3") in desc
+    W = gpu_chains(w, plan=plan, X=Xg)
+    assert torch.equal(W, gpu_chains(w, plan={"threads": 256, "helpers": -1}, X=Xg))
+    check_against_oracle(w, W, label=f"helped k={k} d={d} [{desc}]")
+
+
 BF16_PLANS = [(64, None), (256, None), (512, None), (520, None), (2048, {"block_steps": 4}), (4096, None),
               (8192, {"block_steps": 1}), (16384, None), (30000, None), (65536, None),
               (65536, {"state_in_hbm": 1}), (4100, {"state_in_hbm": 1}), (40000, None), (33000, None),
-              (16384, {"rows": 3}), (30000, {"rows": 3}), (12000, {"rows": 2})]
+              (16384, {"rows": 3}), (30000, {"rows": 3}), (12000, {"rows": 2}),
+              (4096, {"rows": 4}), (2048, {"rows": 4, "block_steps": 2}), (8192, {"rows": 4}), (8000, {"rows": 4}),
+              (1032, {"rows": 4, "block_steps": 2})]
 
 
 @pytest.mark.parametrize("d,plan", BF16_PLANS)
@@ -403,7 +431,8 @@ def _check_from(w, plan, label):
 
 
 @pytest.mark.parametrize("d,plan", [(64, None), (300, None), (4096, None), (4096, {"block_steps": 4}),
-                                    (5000, {"state_in_hbm": 1}), (20000, None), (20000, {"rows": 3})])
+                                    (5000, {"state_in_hbm": 1}), (20000, None), (20000, {"rows": 3}),
+                                    (4096, {"rows": 4}), (2000, {"rows": 4, "block_steps": 2})])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
 def test_dense_chains_from_a_start_vector_and_stream_offsets(d, plan, loss):
     rng = np.random.default_rng(d + 3 * loss)
@@ -489,7 +518,7 @@ def _check_shards(w, plan, label):
 
 
 @pytest.mark.parametrize("d,plan", [(64, None), (300, None), (4096, None), (5000, {"state_in_hbm": 1}), (20000, None),
-                                    (20000, {"rows": 3})])
+                                    (20000, {"rows": 3}), (4096, {"rows": 4}), (2000, {"rows": 4, "block_steps": 2})])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
 def test_dense_chains_on_shuffled_shards(d, plan, loss):
     rng = np.random.default_rng(d + 5 * loss)

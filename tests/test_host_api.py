@@ -125,11 +125,11 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
 
 
 def test_workspace_sizes():
-    # chain order + step counts + stream offsets + share descriptions (256-byte slots) + power table (1 KiB) + shuffled row order (4 bytes a row)
-    # + room for the model vectors in HBM
-    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 2048 + 4096 * 4 + 4 * 64 * 8
+    # chain order + step counts + stream offsets + share descriptions + progress counters (256-byte slots)
+    # + power table (1 KiB) + shuffled row order (4 bytes a row) + room for the model vectors in HBM
+    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 2304 + 4096 * 4 + 4 * 64 * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.HINGE)
     assert ws >= 128 * (1 << 20) * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.LOGISTIC)
-    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 512 + 1024
+    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 1024 + 1024
     assert api.wpsgd_combine_workspace(64, 4096) == 512
