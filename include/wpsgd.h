@@ -84,8 +84,8 @@ typedef struct wpsgd_plan {
                             LDS slots that waves of their own fill from HBM (256 worker threads)       */
     int helpers;         /* dense, 256 threads, k a multiple of 8: workgroups per chain that run ahead of
                             it on otherwise idle compute units and pull its rows into the L2 cache the
-                            chain's compute unit shares.  0: choose (up to 3 when compute units are to
-                            spare and rows are long); -1: none; 1..3: that many, room permitting       */
+                            chain's compute unit shares.  0: choose (2 when compute units are to spare
+                            and rows are 8 KiB or longer); -1: none; 1..3: that many, room permitting  */
 } wpsgd_plan;
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----

@@ -181,7 +181,7 @@ static size_t header_bytes(int k)
 // and only on compute units no chain occupies.
 static int helpers_per_chain(const Plan &p, const wpsgd_matrix *X, int k, const wpsgd_plan *force)
 {
-    if (p.family != Family::DenseReg || p.threads != 256 || p.rows != 1 || k % 8 != 0) return 0;
+    if (p.family != Family::DenseReg || p.threads != 256 || (p.rows != 1 && p.rows != 4) || k % 8 != 0) return 0;
     const int asked = force ? force->helpers : 0;
     if (asked < 0) return 0;
     static int cus = 0;
@@ -192,7 +192,7 @@ static int helpers_per_chain(const Plan &p, const wpsgd_matrix *X, int k, const 
     }
     const int room = (cus - k) / k;
     const int64_t row_bytes = X->d * (X->dtype == WPSGD_BF16 ? 2 : 4);
-    const int want = asked > 0 ? asked : (row_bytes >= 8192 ? 3 : 0);
+    const int want = asked > 0 ? asked : (row_bytes >= 8192 ? 2 : 0);      // a third helper only adds L2 traffic
     return std::max(0, std::min(want, std::min(room, 3)));
 }
 

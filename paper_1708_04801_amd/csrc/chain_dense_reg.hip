@@ -329,7 +329,13 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 TV t = acc[r][0];
 #pragma unroll
                 for (int q = 1; q < NACC; ++q) t += acc[r][q];
-                tot[r] = wave_sum_lane63(t);
+                tot[r] = t;
+            }
+            if constexpr (NR == 3 && sizeof(TV) == 4) {
+                wave_sum3_lane63(tot[0], tot[1], tot[2]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < NR; ++r) tot[r] = wave_sum_lane63(tot[r]);
             }
             if constexpr (NW > 1) {
                 if (lane == kWave - 1) {
@@ -828,6 +834,10 @@ __global__ __launch_bounds__(2 * NT) void chain_dense_fed_kernel(ChainArgs a)
     __shared__ TV red[2][NR][NW];
     __shared__ float ylab[NW][2][kWave];
 
+    if ((int)blockIdx.x >= a.k) {       // a helper workgroup: see run_ahead_of_chain
+        run_ahead_of_chain<TX>(a, reinterpret_cast<uint32_t *>(&ylab[0][0][0]));
+        return;
+    }
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave_all = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -1032,7 +1042,13 @@ __global__ __launch_bounds__(2 * NT) void chain_dense_fed_kernel(ChainArgs a)
                 TV t = acc[r][0];
 #pragma unroll
                 for (int q = 1; q < NACC; ++q) t += acc[r][q];
-                tot[r] = wave_sum_lane63(t);
+                tot[r] = t;
+            }
+            if constexpr (NR == 3 && sizeof(TV) == 4) {
+                wave_sum3_lane63(tot[0], tot[1], tot[2]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < NR; ++r) tot[r] = wave_sum_lane63(tot[r]);
             }
             if (lane == kWave - 1) {
 #pragma unroll
@@ -1097,6 +1113,7 @@ __global__ __launch_bounds__(2 * NT) void chain_dense_fed_kernel(ChainArgs a)
 
         int j0 = 0;
         for (int64_t g = 0; g < npairs; ++g) {
+            if (a.helpers > 0 && tid == 0 && (j0 & 7) == 0) a.progress[blockIdx.x] = (uint32_t)(g * 2 * B);   // for the helpers to see
             if (j0 == 0) {      // a new window of 64 steps begins
                 const int64_t w = (g * 2 * B) / kWave;
                 if (w > 0) {
@@ -1198,7 +1215,8 @@ template <int NT, int EPT, int VEC, int BB, int PP>
 static void launch_variant(const ChainArgs &a, hipStream_t s)
 {
     if constexpr (PP == -2) {
-        hipLaunchKernelGGL((chain_dense_fed_kernel<RowElem, kLoss, NT, EPT, VEC, BB>), dim3(a.k), dim3(2 * NT), 0, s, a);
+        // (its LDS ring leaves room for one workgroup per compute unit, helpers included)
+        hipLaunchKernelGGL((chain_dense_fed_kernel<RowElem, kLoss, NT, EPT, VEC, BB>), dim3(a.k + a.helpers), dim3(2 * NT), 0, s, a);
     } else if constexpr (PP < 0) {
         hipLaunchKernelGGL((chain_dense_lds_kernel<RowElem, kLoss, NT, EPT, VEC>), dim3(a.k), dim3(NT), 0, s, a);
     } else if constexpr (PP == 0) {

@@ -213,6 +213,26 @@ __device__ inline float wave_sum_lane63<float>(float v)
     return v;
 }
 
+// Three fp32 sums at once, level by level: each value's next level is two instructions behind its
+// previous one, which is exactly the distance a DPP operand needs, so no idle slots are spent.
+// Per value the additions and their order are those of wave_sum_lane63.
+__device__ inline void wave_sum3_lane63(float &a, float &b, float &c)
+{
+#define WPSGD_DPP3(CTRL)                                                       \
+    "v_add_f32_dpp %0, %0, %0 " CTRL "\n\t"                                     \
+    "v_add_f32_dpp %1, %1, %1 " CTRL "\n\t"                                     \
+    "v_add_f32_dpp %2, %2, %2 " CTRL "\n\t"
+    asm volatile("s_nop 1\n\t"
+                 WPSGD_DPP3("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1")
+                 WPSGD_DPP3("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1")
+                 WPSGD_DPP3("row_half_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1")
+                 WPSGD_DPP3("row_mirror row_mask:0xf bank_mask:0xf bound_ctrl:1")
+                 WPSGD_DPP3("row_bcast:15 row_mask:0xa bank_mask:0xf")
+                 WPSGD_DPP3("row_bcast:31 row_mask:0xc bank_mask:0xf")
+                 : "+v"(a), "+v"(b), "+v"(c));
+#undef WPSGD_DPP3
+}
+
 __device__ inline float read_lane63(float v)
 {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), kWave - 1));

@@ -161,9 +161,11 @@ def test_dense_fp32_chains(d, loss, plan):
     assert torch.equal(W, W2)                                    # same inputs, same bits
 
 
-@pytest.mark.parametrize("k,d,helpers", [(8, 4096, 3), (16, 4096, 1), (8, 2048, 2), (24, 8192, 0), (8, 1000, 3)])
+@pytest.mark.parametrize("k,d,helpers,extra", [
+    (8, 4096, 3, {}), (16, 4096, 1, {}), (8, 2048, 2, {}), (24, 8192, 0, {}), (8, 1000, 3, {}),
+    (8, 4096, 3, {"rows": 4}), (16, 2048, 2, {"rows": 4, "block_steps": 2}), (8, 8192, 0, {"rows": 4})])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
-def test_dense_chains_with_helper_workgroups(k, d, helpers, loss):
+def test_dense_chains_with_helper_workgroups(k, d, helpers, extra, loss):
     """Workgroups that run ahead of the chains and pull their rows into L2 change when a row arrives,
     never what is computed: same bits as without them, and the oracle's result."""
     rng = np.random.default_rng(k * 31 + d + loss)
@@ -174,11 +176,11 @@ def test_dense_chains_with_helper_workgroups(k, d, helpers, loss):
     n[0], n[1] = 0, 1
     w = wl.Workload("helped", loss, 0.3, 1e-3, 5, n, y, m, d, dense=X)
     Xg = api.matrix_from_workload(w)
-    plan = {"threads": 256, "helpers": helpers}
+    plan = {"threads": 256, "helpers": helpers, **extra}
     desc = api.wpsgd_describe_plan(Xg, k, loss, plan)
-    assert (f"helpers={helpers}" if helpers else "helpers=3") in desc
+    assert (f"helpers={helpers}" if helpers else "helpers=2") in desc
     W = gpu_chains(w, plan=plan, X=Xg)
-    assert torch.equal(W, gpu_chains(w, plan={"threads": 256, "helpers": -1}, X=Xg))
+    assert torch.equal(W, gpu_chains(w, plan={"threads": 256, "helpers": -1, **extra}, X=Xg))
     check_against_oracle(w, W, label=f"helped k={k} d={d} [{desc}]")
 
 
