@@ -65,6 +65,8 @@ def main() -> int:
     ap.add_argument("--block-steps", type=int, default=0)
     ap.add_argument("--prefetch", type=int, default=0)
     ap.add_argument("--state-in-hbm", type=int, default=0)
+    ap.add_argument("--rows", type=int, default=0)
+    ap.add_argument("--helpers", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 "
@@ -88,9 +90,9 @@ def main() -> int:
     y = torch.from_numpy(w.y).cuda()
     k, d = w.k, w.d
     plan = None
-    if args.threads or args.block_steps or args.prefetch or args.state_in_hbm:
+    if args.threads or args.block_steps or args.prefetch or args.state_in_hbm or args.rows or args.helpers:
         plan = {"threads": args.threads, "block_steps": args.block_steps, "prefetch": args.prefetch,
-                "state_in_hbm": args.state_in_hbm}
+                "state_in_hbm": args.state_in_hbm, "rows": args.rows, "helpers": args.helpers}
     desc = api.wpsgd_describe_plan(X, k, w.loss, plan)
     W = torch.empty((k, d), dtype=torch.float32, device="cuda")
     v = torch.empty(d, dtype=torch.float32, device="cuda")
@@ -156,14 +158,16 @@ def main() -> int:
                      "traffic": traffic, "bytes_per_sample_update": bytes_per_update,
                      "kernel_ms": chain_ms, "combine_ms": combine_ms,
                      # a chain is sequential: the launch lasts as long as its longest chain, so this
-                     # per-step time (not the memory system) is what sets the achieved bandwidth
+                     # per-step time is what sets the achieved bandwidth
                      "longest_chain_steps": int(w.n_steps.max()),
                      "us_per_step_longest_chain": chain_ms * 1e3 / max(1, int(w.n_steps.max()))},
         "data_generation_s": t_gen,
     }
 
-    # What the memory side allows with one workgroup per chain: k workgroups streaming rows of
-    # this size with no arithmetic, times the share of that time the chains are alive.
+    # What k compute units can draw from HBM on their own: k workgroups streaming rows of this
+    # size with no arithmetic, times the share of that time the chains are alive.  (One compute
+    # unit draws 55-60 GB/s however much it keeps in flight; the chain kernel gets past this figure
+    # by letting helper workgroups on idle compute units pull the rows into L2 first.)
     if not w.is_csr and w.row_bytes() >= 4096 and w.row_bytes() % 16 == 0:
         rows = int(min(w.n_steps.max(), 4096))
         best = None
@@ -177,7 +181,7 @@ def main() -> int:
             best = ms if best is None else min(best, ms)
         stream_gbs = k * rows * w.row_bytes() / (best * 1e-3) / 1e9
         imbalance = float(w.n_steps.mean() / max(1, w.n_steps.max()))
-        out["roofline"]["one_workgroup_per_chain_ceiling"] = {
+        out["roofline"]["k_compute_units_streaming_alone"] = {
             "streaming_GBps": stream_gbs, "workgroups": k, "alive_fraction": imbalance,
             "attainable_GBps": stream_gbs * imbalance, "frac_of_attainable": achieved / (stream_gbs * imbalance)}
 

@@ -113,14 +113,15 @@ def main():
         "",
         f"Achieved (algorithmic) bandwidth {roof['achieved']:.1f} GB/s = {100 * roof['frac']:.2f} % of the 8 TB/s peak.",
     ]
-    ceil = roof.get("one_workgroup_per_chain_ceiling")
+    ceil = roof.get("k_compute_units_streaming_alone")
     if ceil:
         lines += [
             "",
-            f"Streaming ceiling of this mapping (`stream_rows_kernel`, {ceil['workgroups']} workgroups, no arithmetic): "
+            f"What {ceil['workgroups']} compute units draw from HBM on their own (`stream_rows_kernel`, no arithmetic): "
             f"{ceil['streaming_GBps']:.1f} GB/s; chains are alive {100 * ceil['alive_fraction']:.1f} % of the kernel's "
-            f"duration on average, so the memory side allows {ceil['attainable_GBps']:.1f} GB/s; the chain kernel reaches "
-            f"{100 * ceil['frac_of_attainable']:.1f} % of that.",
+            f"duration on average, which would allow {ceil['attainable_GBps']:.1f} GB/s; the chain kernel reaches "
+            f"{100 * ceil['frac_of_attainable']:.1f} % of that (more than all of it where helper workgroups on idle "
+            "compute units pull the rows into L2 ahead of the chains).",
         ]
     if "us_per_step_longest_chain" in roof:
         lines += ["", f"Longest chain: {roof['longest_chain_steps']} steps, {roof['us_per_step_longest_chain']:.3f} us per step "
