@@ -73,7 +73,21 @@ static int dense_vec(const wpsgd_matrix *X)
 
 // Chooses the kernel family and its parameters.  Dense rows go to the register kernel when
 // some instantiated shape holds d elements, else to the HBM-state kernel.
-static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan *force, Plan *out,
+static int compute_units()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return 256;                 // no device to ask (planning on a host without one): the target's count
+        }
+        cus = n;
+    }
+    return cus;
+}
+
+static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *force, Plan *out,
                         double rho = 1.0, int64_t max_steps = 0)
 {
     Plan p{};
@@ -134,6 +148,20 @@ static int resolve_plan(const wpsgd_matrix *X, wpsgd_loss loss, const wpsgd_plan
                 q.prefetch = f.prefetch;
                 q.rows = f.rows;
                 q.state_bytes_per_elem = 0;
+                // Few chains of 16 KiB fp32 rows, each alone on a compute unit, are bound by the
+                // latency of a step: two steps per reduction round (three sums instead of two, one
+                // exchange instead of two) are 8 % faster there.  With more chains than compute
+                // units the extra Gram products would only cost throughput.
+                if (!f.block_steps && !f.prefetch && !f.rows && nt == 256 && ept == 16 && vec == 4 &&
+                    p.loss == WPSGD_LOGISTIC && p.dtype == WPSGD_F32 && k <= compute_units()) {
+                    Plan two = q;
+                    two.block_steps = 2;
+                    two.prefetch = 4;
+                    if (dense_reg_dispatch(two, nullptr, nullptr) == hipSuccess) {
+                        *out = two;
+                        return WPSGD_OK;
+                    }
+                }
                 if (dense_reg_dispatch(q, nullptr, nullptr) == hipSuccess) {
                     *out = q;
                     return WPSGD_OK;
@@ -184,13 +212,7 @@ static int helpers_per_chain(const Plan &p, const wpsgd_matrix *X, int k, const 
     if (p.family != Family::DenseReg || p.threads != 256 || (p.rows != 1 && p.rows != 4) || k % 8 != 0) return 0;
     const int asked = force ? force->helpers : 0;
     if (asked < 0) return 0;
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-        cus = n;
-    }
-    const int room = (cus - k) / k;
+    const int room = (compute_units() - k) / k;
     const int64_t row_bytes = X->d * (X->dtype == WPSGD_BF16 ? 2 : 4);
     const int want = asked > 0 ? asked : (row_bytes >= 8192 ? 2 : 0);      // a third helper only adds L2 traffic
     return std::max(0, std::min(want, std::min(room, 3)));
@@ -269,7 +291,7 @@ size_t wpsgd_run_chains_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss,
     if (check_matrix(X) != WPSGD_OK || k < 1) return 0;
     if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return 0;
     Plan p;
-    if (resolve_plan(X, loss, plan, &p) != WPSGD_OK) return 0;
+    if (resolve_plan(X, k, loss, plan, &p) != WPSGD_OK) return 0;
     // Always room for the model vectors in HBM: which kernel runs also depends on eta*lambda,
     // which this query does not see.
     return header_bytes(k) + perm_bytes(X->m) + align256((size_t)k * (size_t)X->d * state_elem_bytes(loss));
@@ -283,7 +305,7 @@ int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     if (rc != WPSGD_OK) return rc;
     if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
     Plan p;
-    rc = resolve_plan(X, loss, plan, &p);
+    rc = resolve_plan(X, k, loss, plan, &p);
     if (rc != WPSGD_OK) return rc;
     static const char *const kRows[] = {"", " rows=registers", " rows=lds", " rows=twice", " rows=fed"};
     char helped[32] = "";
@@ -326,7 +348,7 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     Plan p;
     int64_t max_steps = 0;
     for (int i = 0; i < k; ++i) max_steps = std::max(max_steps, n_steps[i]);
-    rc = resolve_plan(X, loss, plan, &p, 1.0 - eta * lambda, max_steps);
+    rc = resolve_plan(X, k, loss, plan, &p, 1.0 - eta * lambda, max_steps);
     if (rc != WPSGD_OK) return rc;
     const size_t need = header_bytes(k) + perm_bytes(X->m) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
     if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;

@@ -273,12 +273,20 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 rx[b] = make_rsrc(reinterpret_cast<const void *>((hi << 32) | lo), row_bytes);
             }
         };
-        auto issue = [&](int u, const __amdgpu_buffer_rsrc_t (&rx)[B]) {
+        // requests rows b_lo .. b_hi-1 of a round into slot u
+        auto issue_rows = [&](int u, const __amdgpu_buffer_rsrc_t (&rx)[B], int b_lo, int b_hi) {
 #pragma unroll
             for (int b = 0; b < B; ++b)
 #pragma unroll
-                for (int c = 0; c < Frag::kChunks; ++c) x[u][b].load_chunk(c, rx[b], off[c]);
+                for (int c = 0; c < Frag::kChunks; ++c)
+                    if (b >= b_lo && b < b_hi) x[u][b].load_chunk(c, rx[b], off[c]);
         };
+        auto issue = [&](int u, const __amdgpu_buffer_rsrc_t (&rx)[B]) { issue_rows(u, rx, 0, B); };
+        // A round's requests are issued in two halves, the first while the workgroup's sums travel
+        // back, the second after the update: the four waves' requests for one row keep the CU's
+        // address path busy for 256 cycles, and a wave that wants to issue behind a longer queue
+        // than that stands still (two rows at once cost 17 % at d = 4096).
+        constexpr int kFirstHalf = (B + 1) / 2;
         auto request = [&](int u, int j) {
             __amdgpu_buffer_rsrc_t rx[B];
             describe(j, rx);
@@ -361,7 +369,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 for (int r = 0; r < NR; ++r)
 #pragma unroll
                     for (int w = 0; w < NW; ++w) part[r][w] = red[parity][r][w];
-                if constexpr (P > 1) issue(u_prev, next_rows);
+                if constexpr (P > 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
 #pragma unroll
                 for (int r = 0; r < NR; ++r) {
                     TV t = part[r][0];
@@ -371,7 +379,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 }
                 parity ^= 1;
             } else {
-                if constexpr (P > 1) issue(u_prev, next_rows);
+                if constexpr (P > 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
 #pragma unroll
                 for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
             }
@@ -399,6 +407,10 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             for (int e = 0; e < EPT; ++e) {
 #pragma unroll
                 for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
+            }
+            if constexpr (P > 1 && kFirstHalf < B) {
+                __builtin_amdgcn_sched_barrier(0);        // keep these requests behind the update
+                issue_rows(u_prev, next_rows, kFirstHalf, B);
             }
             if constexpr (P == 1) {                       // a single slot: refill once it is free
                 __amdgpu_buffer_rsrc_t rx[B];
