@@ -532,6 +532,22 @@ def test_dense_chains_on_shuffled_shards(d, plan, loss):
     _check_shards(w, plan, f"dense d={d} {plan}")
 
 
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+@pytest.mark.parametrize("plan", [{"threads": 256, "helpers": 2}, {"threads": 256, "helpers": 1, "rows": 4}])
+def test_helped_chains_from_offsets_and_on_shards(plan, loss):
+    """Helper workgroups walk the same sample stream as their chain under every sampling mode:
+    a start vector with per-chain stream offsets, and partition-and-shuffle sampling."""
+    rng = np.random.default_rng(17 + loss)
+    m, d, k = 401, 4096, 8
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = np.array([130, 0, 75, 200, 64, 1, 333, 90], dtype=np.int64)
+    w = wl.Workload("helped_from", loss, 0.3, 1e-2, 21, n, y, m, d, dense=X)
+    assert "helpers=" in api.wpsgd_describe_plan(api.matrix_from_workload(w), k, loss, plan)
+    _check_from(w, plan, f"helped from {plan}")
+    _check_shards(w, plan, f"helped shards {plan}")
+
+
 @pytest.mark.parametrize("plan", SPARSE_PLANS)
 def test_sparse_chains_on_shuffled_shards(plan):
     w = wl.sparse_hinge(m=3000, d=1 << 14, k=5, n_median=150)
