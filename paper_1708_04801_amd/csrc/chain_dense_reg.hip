@@ -92,10 +92,11 @@ struct RowFrag {
 // multiple of 8 helper k*q + b and chain workgroup b share an XCD; the q-th of a chain's Q helpers
 // takes the steps t with t mod Q = q.  The chain publishes how far it has come; a helper stays
 // between kLeadMin and kLeadMax steps ahead of that (far enough to beat the chain's own requests,
-// close enough that the lines are still cached when they are used) and gives up when the chain
-// does not move, so it ends whatever the chain does.  The touched data lands in a scratch corner
+// close enough that the lines are still cached when they are used), stops when the chain says it
+// has finished, and gives up when the chain does not move, so it ends whatever the chain does.  The touched data lands in a scratch corner
 // of LDS and is never read.
 constexpr int kLeadMin = 10, kLeadMax = 26;
+constexpr uint32_t kChainDone = 0xFFFFFFFFu;      // published by a chain that has finished
 
 template <typename TX>
 __device__ inline void run_ahead_of_chain(const ChainArgs &a, uint32_t *lds_sink)
@@ -115,19 +116,19 @@ __device__ inline void run_ahead_of_chain(const ChainArgs &a, uint32_t *lds_sink
     typedef __attribute__((address_space(3))) uint32_t *lds_ptr;
     const uint32_t sink = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)(lds_ptr)lds_sink);
     uint32_t seen = 0;                                   // steps the chain has completed, as last read
-    int64_t polls = n + (1 << 20);                       // every wait below draws on this
+    int64_t polls = n / 4 + (1 << 15);                   // every wait below draws on this
     bool alive = true;
     for (int64_t w0 = 0; w0 < n && alive; w0 += kWave) {
         const uint32_t rows = sample_window(a.seed_lo, a.seed_hi, (uint32_t)chain, step0 + w0, (uint32_t)a.m, a.perm,
                                             (uint32_t)a.k);
         for (int j = (int)((q + Q - (int)(w0 % Q)) % Q); j < kWave && w0 + j < n; j += Q) {
             const uint32_t t = (uint32_t)(w0 + j);
-            while ((int32_t)(t - seen) > kLeadMax && polls > 0) {
+            while (seen != kChainDone && (int32_t)(t - seen) > kLeadMax && polls > 0) {
                 seen = __hip_atomic_load(progress, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 --polls;
-                if ((int32_t)(t - seen) > kLeadMax) __builtin_amdgcn_s_sleep(16);
+                if (seen != kChainDone && (int32_t)(t - seen) > kLeadMax) __builtin_amdgcn_s_sleep(16);
             }
-            if (polls <= 0) {
+            if (polls <= 0 || seen == kChainDone) {      // the chain does not move, or has finished
                 alive = false;
                 break;
             }
@@ -468,6 +469,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             j0 = (j0 + D) & (kWave - 1);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);      // no label load may still be on its way to LDS when the wave ends
+        if (a.helpers > 0 && tid == 0) a.progress[blockIdx.x] = kChainDone;
         // scale at the chain's end: s_w covers the steps before the last window
         const int64_t last_w = (n - 1) / kWave;
         const int rem = (int)(n - last_w * kWave);                          // 1..64 steps in it
@@ -1159,6 +1161,7 @@ __global__ __launch_bounds__(2 * NT) void chain_dense_fed_kernel(ChainArgs a)
             j0 = (j0 + 2 * B) & (kWave - 1);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (a.helpers > 0 && tid == 0) a.progress[blockIdx.x] = kChainDone;
         const int64_t last_w = (n - 1) / kWave;
         const int rem = (int)(n - last_w * kWave);
         const double s_end = s_w * lane_read(rho_pow, rem - 1) * rho;
