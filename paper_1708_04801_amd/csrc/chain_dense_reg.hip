@@ -381,8 +381,12 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 parity ^= 1;
             } else {
                 if constexpr (P > 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
+                // One wave: the sums sit in lane 63.  The hinge only needs one bit of them, which
+                // is read off the comparison below; the logistic slope needs the value in every lane.
+                if constexpr (LOSS != kLossHinge) {
 #pragma unroll
-                for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
+                    for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
+                }
             }
             // the B dependent steps, as scalars
             TV c[B];
@@ -398,7 +402,13 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                         ++g;
                     }
                 if constexpr (LOSS == kLossHinge) {
-                    c[b] = (zy[b] * dot < 1.0) ? cy[b] : 0.0;              // -eta*g/s_next, g = -y or 0
+                    // -eta*g/s_next, g = -y or 0
+                    if constexpr (NW > 1) {
+                        c[b] = (zy[b] * dot < 1.0) ? cy[b] : 0.0;
+                    } else {
+                        const bool inside = (__builtin_amdgcn_ballot_w64(zy[b] * dot < 1.0) >> (kWave - 1)) != 0;   // lane 63's verdict
+                        c[b] = inside ? cy[b] : 0.0;
+                    }
                 } else {
                     // -eta*g/s_next with g = -y/(1+exp(y*yhat)); exp as 2^(log2(e)*y*s*dot)
                     c[b] = cy[b] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(zy[b] * dot));
