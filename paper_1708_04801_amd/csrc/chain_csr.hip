@@ -279,12 +279,12 @@ __global__ __launch_bounds__(kWave) void chain_csr_cached_kernel(ChainArgs a)
             const TV cur = (in && xc < kHead) ? head[xc] : hidden_load(in ? v + xc : dump);
             if (in) acc += cur * (TV)xv;
         }
-        acc = wave_sum(acc);
         const TV zs = lane_read(zs_tab, j), cs = lane_read(cs_tab, j);      // label folded in
         TV coef;
         if constexpr (LOSS == kLossHinge) {
-            coef = (zs * acc < 1.0) ? cs : 0.0;
+            coef = lane63_below_one(zs, wave_sum_lane63(acc)) ? cs : 0.0;
         } else {
+            acc = wave_sum(acc);
             coef = cs * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(zs * acc));
         }
 #pragma unroll

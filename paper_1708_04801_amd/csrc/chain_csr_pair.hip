@@ -414,11 +414,11 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                             if (in) acc += cur * (TV)xv;
                         }
                     }
-                    acc = wave_sum(acc);
                     TV coef;
                     if constexpr (LOSS == kLossHinge) {
-                        coef = (sc.zs * acc < 1.0) ? sc.cs : 0.0;
+                        coef = lane63_below_one(sc.zs, wave_sum_lane63(acc)) ? sc.cs : 0.0;
                     } else {
+                        acc = wave_sum(acc);
                         coef = sc.cs * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc.zs * acc));
                     }
 #pragma unroll

@@ -293,8 +293,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     if constexpr (NW > 1) {
                         c[b] = (zy[b] * dot < 1.0) ? cy[b] : 0.0;
                     } else {
-                        const bool inside = (__builtin_amdgcn_ballot_w64(zy[b] * dot < 1.0) >> (kWave - 1)) != 0;   // lane 63's verdict
-                        c[b] = inside ? cy[b] : 0.0;
+                        c[b] = lane63_below_one(zy[b], dot) ? cy[b] : 0.0;
                     }
                 } else {
                     // -eta*g/s_next with g = -y/(1+exp(y*yhat)); exp as 2^(log2(e)*y*s*dot)

@@ -246,6 +246,13 @@ __device__ inline double read_lane63(double v)
     return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
 }
 
+// Is zs * (value in lane 63) < 1?  The hinge step of a one-wave chain needs only this one bit of the
+// wave's sum, so the sum is not broadcast first: every lane compares, lane 63's answer counts.
+__device__ inline bool lane63_below_one(double zs, double sum_in_lane63)
+{
+    return (__builtin_amdgcn_ballot_w64(zs * sum_in_lane63 < 1.0) >> (kWave - 1)) != 0;
+}
+
 // Sum over the 64 lanes, result in every lane.
 template <typename T>
 __device__ inline T wave_sum(T v)
