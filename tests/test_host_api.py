@@ -122,6 +122,18 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
     with pytest.raises(api.WpsgdError) as err:
         d(_FakeMatrix(100, 256), 2, api.HINGE, plan={"threads": 64, "block_steps": 8})
     assert err.value.status == api.UNSUPPORTED
+    # few fp32 logistic chains of 16 KiB rows: two steps per reduction round, helpers on the idle compute units
+    few = d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC)
+    assert "B=2 P=4" in few and "helpers=2" in few
+    many = d(_FakeMatrix(262144, 4096), 2048, api.LOGISTIC)
+    assert "B=1 P=8" in many and "helpers" not in many
+    assert "helpers" not in d(_FakeMatrix(262144, 4096), 63, api.LOGISTIC)           # k not a multiple of 8
+    assert "helpers" not in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"helpers": -1})
+    assert "rows=fed" in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"rows": 4})
+    for bad in ({"helpers": 4}, {"helpers": -2}, {"rows": 5}):
+        with pytest.raises(api.WpsgdError) as err:
+            d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan=bad)
+        assert err.value.status == api.INVALID_ARG
 
 
 def test_workspace_sizes():
