@@ -201,15 +201,14 @@ constexpr size_t kPowTabBytes = 2 * 64 * sizeof(double);
 static size_t header_bytes(int k)
 {
     return align256((size_t)k * sizeof(int32_t)) + 2 * align256((size_t)k * sizeof(int64_t)) +
-           align256((size_t)k * 3 * sizeof(uint32_t)) + align256((size_t)k * sizeof(uint32_t)) + kPowTabBytes;
+           align256((size_t)k * 3 * sizeof(uint32_t)) + align256(((size_t)k * 2 + 16) * sizeof(uint32_t)) + kPowTabBytes;
 }
 
 // Helper workgroups per chain for a resolved plan: only the 256-thread register kernels have
-// them, only when k is a multiple of 8 (workgroups b and b+k then share an XCD and its L2 cache),
-// and only on compute units no chain occupies.
+// them, and only on compute units no chain occupies (at most 128 chains).
 static int helpers_per_chain(const Plan &p, const wpsgd_matrix *X, int k, const wpsgd_plan *force)
 {
-    if (p.family != Family::DenseReg || p.threads != 256 || (p.rows != 1 && p.rows != 4) || k % 8 != 0) return 0;
+    if (p.family != Family::DenseReg || p.threads != 256 || (p.rows != 1 && p.rows != 4) || k > 128) return 0;
     const int asked = force ? force->helpers : 0;
     if (asked < 0) return 0;
     const int room = (compute_units() - k) / k;

@@ -46,6 +46,7 @@ __global__ __launch_bounds__(2 * NT) void chain_dense_fed_kernel(ChainArgs a)
         return;
     }
     const int tid = threadIdx.x;
+    if (a.helpers > 0 && tid == 0) announce_chain_workgroup(a);
     const int lane = tid & (kWave - 1);
     const int wave_all = __builtin_amdgcn_readfirstlane(tid / kWave);
     const bool mover = wave_all >= NW;

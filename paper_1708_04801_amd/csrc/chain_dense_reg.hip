@@ -61,6 +61,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         return;
     }
     const int tid = threadIdx.x;
+    if (a.helpers > 0 && tid == 0) announce_chain_workgroup(a);
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const int chain = a.order[blockIdx.x];

@@ -57,23 +57,78 @@ struct RowFrag {
 // of every 128-byte line of the rows the chain will visit, so that they sit in the L2 cache of the
 // chain's XCD when the chain asks for them.  One compute unit draws some 55-60 GB/s from HBM however
 // many loads it keeps in flight, which for 16 KiB rows is no faster than a chain can consume them;
-// out of L2 it draws more than twice that.  Workgroups are handed to the XCDs in turn, so with k a
-// multiple of 8 helper k*q + b and chain workgroup b share an XCD; the q-th of a chain's Q helpers
-// takes the steps t with t mod Q = q.  The chain publishes how far it has come; a helper stays
-// between kLeadMin and kLeadMax steps ahead of that (far enough to beat the chain's own requests,
-// close enough that the lines are still cached when they are used), stops when the chain says it
-// has finished, and gives up when the chain does not move, so it ends whatever the chain does.  The touched data lands in a scratch corner
-// of LDS and is never read.
+// out of L2 it draws more than twice that.
+//
+// Who helps whom is settled on the device, because only there is it known which XCD a workgroup
+// landed on.  Every chain workgroup writes its XCD number (plus one) next to its progress counter.
+// A helper reads its own, waits (within a budget) until every chain has written, takes the next
+// free seat of its XCD with an atomic increment, and serves the chains of that XCD in turn: seat
+// r goes to chain r mod (chains on this XCD) as that chain's (r div chains)-th helper, and the
+// q-th of a chain's Q helpers takes the steps t with t mod Q = q.  Helpers beyond Q per chain
+// leave.  The chain publishes how far it has come; a helper stays between kLeadMin and kLeadMax
+// steps ahead of that (far enough to beat the chain's own requests, close enough that the lines
+// are still cached when they are used), stops when the chain says it has finished, and gives up
+// when the chain does not move, so it ends whatever the chain does.  The touched data lands in a
+// scratch corner of LDS and is never read.
+//
+// Header words used (all zero at launch): progress[b] for chain workgroup b, progress[k + b] its
+// XCD number plus one, progress[2k + x] the seats taken on XCD x.
 constexpr int kLeadMin = 10, kLeadMax = 26;
 constexpr uint32_t kChainDone = 0xFFFFFFFFu;      // published by a chain that has finished
+constexpr int kMaxXcds = 16;
+
+__device__ inline uint32_t xcd_of_this_wave()
+{
+    uint32_t x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    return x & 0xfu;
+}
+
+// called by thread 0 of a chain workgroup before its first step.  Helpers on every XCD read this
+// word and each XCD has an L2 cache of its own, so it is stored at device scope (written through);
+// the progress counter is only read by helpers of the same XCD and takes plain stores.
+__device__ inline void announce_chain_workgroup(const ChainArgs &a)
+{
+    __hip_atomic_store(a.progress + a.k + blockIdx.x, xcd_of_this_wave() + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// index of the n-th set bit (n counted from 0) of a mask that has more than n bits set
+__device__ inline int nth_set_bit(uint64_t mask, int n)
+{
+    for (int i = 0; i < n; ++i) mask &= mask - 1;
+    return __builtin_ctzll(mask);
+}
 
 template <typename TX>
 __device__ inline void run_ahead_of_chain(const ChainArgs &a, uint32_t *lds_sink)
 {
     if (threadIdx.x >= kWave) return;                    // one wave does it
     const int lane = (int)threadIdx.x;
-    const int h = (int)blockIdx.x - a.k;
-    const int b = h % a.k, q = h / a.k, Q = a.helpers / a.k;
+    const int Q = a.helpers / a.k;
+    // which chains run on this XCD?  (k <= 128: two header words per lane)
+    const uint32_t here = xcd_of_this_wave() + 1u;
+    const uint32_t *where = a.progress + a.k;
+    uint64_t on0 = 0, on1 = 0;
+    bool all = false;
+    for (int tries = 0; tries < (1 << 14) && !all; ++tries) {
+        const uint32_t x0 = lane < a.k ? __hip_atomic_load(where + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0u;
+        const uint32_t x1 = lane + kWave < a.k
+                                ? __hip_atomic_load(where + lane + kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                : ~0u;
+        all = __builtin_amdgcn_ballot_w64(x0 != 0u && x1 != 0u) == ~0ull;
+        on0 = __builtin_amdgcn_ballot_w64(x0 == here);
+        on1 = __builtin_amdgcn_ballot_w64(x1 == here);
+        if (!all) __builtin_amdgcn_s_sleep(16);
+    }
+    const int n_here = __builtin_popcountll(on0) + __builtin_popcountll(on1);
+    if (!all || n_here == 0) return;                     // chains not running yet, or none of them here
+    uint32_t seat = 0;
+    if (lane == 0) seat = atomicAdd(a.progress + 2 * a.k + (here - 1u), 1u);
+    seat = (uint32_t)__builtin_amdgcn_readfirstlane((int)seat);
+    const int q = (int)seat / n_here, which = (int)seat % n_here;
+    if (q >= Q) return;                                  // this XCD's chains have their helpers
+    const int first = __builtin_popcountll(on0);
+    const int b = which < first ? nth_set_bit(on0, which) : kWave + nth_set_bit(on1, which - first);
     const int chain = a.order[b];
     const int64_t n = a.nsteps[b];
     const int64_t step0 = a.step0[b];

@@ -36,9 +36,11 @@ struct ChainArgs {
     double eta, rho;          // rho = 1 - eta*lambda
     uint32_t seed_lo, seed_hi;
     // Helper workgroups (dense register kernels): workgroups k .. k+helpers-1 run ahead of the
-    // chains and pull their rows into the L2 cache; helpers is a multiple of k (or 0).
+    // chains and pull their rows into the L2 cache; helpers is a multiple of k (or 0, and only
+    // for k <= 128).
     int helpers;
-    uint32_t *progress;       // DEVICE, k entries, zero at launch: steps workgroup b has completed (low 32 bits)
+    uint32_t *progress;       // DEVICE, 2k+16 entries, zero at launch: [b] steps workgroup b has completed
+                              // (low 32 bits), [k+b] its XCD number plus one, [2k+x] helper seats taken on XCD x
     // outputs / scratch
     float *W;                 // k x d
     void *state;              // k x d model vectors in HBM (state_in_hbm plans), else unused

@@ -163,7 +163,8 @@ def test_dense_fp32_chains(d, loss, plan):
 
 @pytest.mark.parametrize("k,d,helpers,extra", [
     (8, 4096, 3, {}), (16, 4096, 1, {}), (8, 2048, 2, {}), (24, 8192, 0, {}), (8, 1000, 3, {}),
-    (8, 4096, 3, {"rows": 4}), (16, 2048, 2, {"rows": 4, "block_steps": 2}), (8, 8192, 0, {"rows": 4})])
+    (8, 4096, 3, {"rows": 4}), (16, 2048, 2, {"rows": 4, "block_steps": 2}), (8, 8192, 0, {"rows": 4}),
+    (9, 4096, 2, {}), (13, 4096, 3, {"block_steps": 1}), (70, 2048, 1, {}), (3, 4096, 3, {"rows": 4})])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
 def test_dense_chains_with_helper_workgroups(k, d, helpers, extra, loss):
     """Workgroups that run ahead of the chains and pull their rows into L2 change when a row arrives,

@@ -127,7 +127,9 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
     assert "B=2 P=4" in few and "helpers=2" in few
     many = d(_FakeMatrix(262144, 4096), 2048, api.LOGISTIC)
     assert "B=1 P=8" in many and "helpers" not in many
-    assert "helpers" not in d(_FakeMatrix(262144, 4096), 63, api.LOGISTIC)           # k not a multiple of 8
+    assert "helpers=2" in d(_FakeMatrix(262144, 4096), 63, api.LOGISTIC)
+    assert "helpers=1" in d(_FakeMatrix(262144, 4096), 128, api.LOGISTIC)            # one spare compute unit per chain
+    assert "helpers" not in d(_FakeMatrix(262144, 4096), 129, api.LOGISTIC)
     assert "helpers" not in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"helpers": -1})
     assert "rows=fed" in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"rows": 4})
     for bad in ({"helpers": 4}, {"helpers": -2}, {"rows": 5}):
@@ -143,5 +145,5 @@ def test_workspace_sizes():
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.HINGE)
     assert ws >= 128 * (1 << 20) * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.LOGISTIC)
-    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 1024 + 1024
+    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 2048 + 1024
     assert api.wpsgd_combine_workspace(64, 4096) == 512
