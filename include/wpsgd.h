@@ -86,6 +86,11 @@ typedef struct wpsgd_plan {
                             it on otherwise idle compute units and pull its rows into the L2 cache the
                             chain's compute unit shares.  0: choose (2 when compute units are to spare
                             and rows are 8 KiB or longer); -1: none; 1..3: that many, room permitting  */
+    int slices;          /* dense, 256 threads, rows in registers: compute units per chain.  Each takes a
+                            slice of 256 x (elements per thread) columns of the model vector and of every
+                            row; the slices add their partial sums through global memory once per round
+                            (logistic: 1 or 2 steps per round; hinge: 1).  0: choose; 1: a chain is one
+                            workgroup; 2..8: that many, which must be what the shape needs to cover d     */
 } wpsgd_plan;
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----

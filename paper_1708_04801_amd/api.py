@@ -40,7 +40,7 @@ class _CMatrix(ctypes.Structure):
 class _CPlan(ctypes.Structure):
     _fields_ = [("threads", ctypes.c_int), ("block_steps", ctypes.c_int),
                 ("prefetch", ctypes.c_int), ("state_in_hbm", ctypes.c_int),
-                ("rows", ctypes.c_int), ("helpers", ctypes.c_int)]
+                ("rows", ctypes.c_int), ("helpers", ctypes.c_int), ("slices", ctypes.c_int)]
 
 
 class WpsgdError(RuntimeError):
@@ -144,6 +144,7 @@ def _plan(plan):
     p.state_in_hbm = int(plan.get("state_in_hbm", 0))
     p.rows = int(plan.get("rows", 0))
     p.helpers = int(plan.get("helpers", 0))
+    p.slices = int(plan.get("slices", 0))
     return ctypes.byref(p)
 
 

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     // Labels of a whole window, gathered straight into LDS one window ahead (per wave, two windows)
     __shared__ float ylab[NW][2][kWave];
 
-    if ((int)blockIdx.x >= a.k) {       // a helper workgroup: see run_ahead_of_chain
+    if ((int)blockIdx.x >= a.k * a.slices) {       // a helper workgroup: see run_ahead_of_chain
         run_ahead_of_chain<TX>(a, reinterpret_cast<uint32_t *>(&ylab[0][0][0]));
         return;
     }
@@ -64,25 +64,32 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     if (a.helpers > 0 && tid == 0) announce_chain_workgroup(a);
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    const int chain = a.order[blockIdx.x];
-    const int64_t n = a.nsteps[blockIdx.x];
+    // Workgroup cb + s*k runs column slice s of the chain of workgroup cb: columns
+    // [s*NT*EPT, (s+1)*NT*EPT) of the model vector and of every row.  One slice is the whole chain.
+    const int cb = a.slices > 1 ? (int)(blockIdx.x % (unsigned)a.k) : (int)blockIdx.x;
+    const int slice = a.slices > 1 ? (int)(blockIdx.x / (unsigned)a.k) : 0;
+    const int64_t col0 = (int64_t)slice * (NT * EPT);
+    const int chain = a.order[cb];
+    const int64_t n = a.nsteps[cb];
     const char *X = static_cast<const char *>(a.dense);
     const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
     const uint32_t row_bytes = (uint32_t)(a.d * (int64_t)sizeof(TX));
     float *out = a.W + (int64_t)chain * a.d;
+    bool lost = false;                  // set when the other slices of the chain did not show up
 
     TV v[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-        const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
+        const int64_t col = col0 + ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
         v[e] = (a.w_start && col < a.d) ? (TV)a.w_start[col] : (TV)0;
     }
-    const int64_t step0 = a.step0[blockIdx.x];
+    const int64_t step0 = a.step0[cb];
 
     if (n > 0) {
         uint32_t off[Frag::kChunks];               // this lane's byte offset of each chunk
 #pragma unroll
-        for (int c = 0; c < Frag::kChunks; ++c) off[c] = (uint32_t)(((c * NT + tid) * VEC) * sizeof(TX));
+        for (int c = 0; c < Frag::kChunks; ++c)
+            off[c] = (uint32_t)((col0 + (c * NT + tid) * VEC) * (int64_t)sizeof(TX));
         Frag x[P][B];
 
         // (1-eta*lambda)^lane and (1-eta*lambda)^-(lane+1), by binary powering in fp64
@@ -105,9 +112,9 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         // division sits in the loop.  Windows are asked for in order: 0, 1, 2, ...
         uint32_t shard_lo = 0, shard_len = 1, shard_inc = 0, shard_pos = 0;
         if (a.perm) {
-            shard_lo = a.shard[blockIdx.x];
-            shard_len = a.shard[a.k + blockIdx.x];
-            const uint32_t pos0 = a.shard[2 * a.k + blockIdx.x], room = shard_len - pos0;
+            shard_lo = a.shard[cb];
+            shard_len = a.shard[a.k + cb];
+            const uint32_t pos0 = a.shard[2 * a.k + cb], room = shard_len - pos0;
             shard_inc = (uint32_t)kWave % shard_len;
             shard_pos = (uint32_t)lane < room ? pos0 + (uint32_t)lane : ((uint32_t)lane - room) % shard_len;
         }
@@ -197,6 +204,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         request_labels(0, rows_a);
         request_labels(1, rows_b);
 
+        uint32_t round_no = 0;              // rounds done, as the slices of a chain count them
+        const bool near_slices = a.slices > 1 && slices_share_an_xcd(a, cb, slice, tid == 0);
         int parity = 0;
         // One round: steps at in-window positions j .. j+B-1, rows in slot u.  While the partial
         // sums cross the workgroup, slot u_prev (consumed one round ago) is requested again for
@@ -276,6 +285,36 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     for (int r = 0; r < NR; ++r) tot[r] = read_lane63(tot[r]);
                 }
             }
+            // several slices: add up the slices' sums (every wave of every slice ends with the same totals)
+            if constexpr (NW > 1 && NR * sizeof(TV) <= kSliceMaxWords * 4) {
+                if (a.slices > 1) {
+                    uint32_t w[kSliceMaxWords];
+#pragma unroll
+                    for (int q = 0; q < kSliceMaxWords; ++q) w[q] = 0u;
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        if constexpr (sizeof(TV) == 8) {
+                            const uint64_t bits = (uint64_t)__double_as_longlong((double)tot[r]);
+                            w[2 * r] = (uint32_t)bits;
+                            w[2 * r + 1] = (uint32_t)(bits >> 32);
+                        } else {
+                            w[r] = __float_as_uint((float)tot[r]);
+                        }
+                    }
+                    const bool met = near_slices ? slices_all_reduce<sizeof(TV) == 8, NR, true>(a, cb, slice, tid == 0, round_no, w)
+                                                 : slices_all_reduce<sizeof(TV) == 8, NR, false>(a, cb, slice, tid == 0, round_no, w);
+                    if (!met) lost = true;
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        if constexpr (sizeof(TV) == 8) {
+                            tot[r] = (TV)__longlong_as_double((long long)(((uint64_t)w[2 * r + 1] << 32) | w[2 * r]));
+                        } else {
+                            tot[r] = (TV)__uint_as_float(w[r]);
+                        }
+                    }
+                    ++round_no;
+                }
+            }
             // the B dependent steps, as scalars
             TV c[B];
 #pragma unroll
@@ -332,7 +371,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         const int64_t ngroups = (nblk + P - 1) / P;
         int j0 = 0;                                 // in-window position of the group's first step
         for (int64_t g = 0; g < ngroups; ++g) {
-            if (a.helpers > 0 && tid == 0) a.progress[blockIdx.x] = (uint32_t)(g * D);   // for the helpers to see
+            if (a.helpers > 0 && tid == 0) a.progress[cb] = (uint32_t)(g * D);   // for the helpers to see
             if (j0 == 0) {      // a new window of 64 steps begins (never in the middle of a group)
                 const int64_t w = (g * D) / kWave;
                 if (w > 0) {
@@ -364,9 +403,10 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             for (int u = 0; u < P; ++u)
                 round(u, j0 + u * B, (u + P - 1) % P);
             j0 = (j0 + D) & (kWave - 1);
+            if (lost) break;                        // (uniform within a wave)
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);      // no label load may still be on its way to LDS when the wave ends
-        if (a.helpers > 0 && tid == 0) a.progress[blockIdx.x] = kChainDone;
+        if (a.helpers > 0 && tid == 0) a.progress[cb] = kChainDone;
         // scale at the chain's end: s_w covers the steps before the last window
         const int64_t last_w = (n - 1) / kWave;
         const int rem = (int)(n - last_w * kWave);                          // 1..64 steps in it
@@ -377,8 +417,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-        const int64_t col = ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
-        if (col < a.d) out[col] = (float)v[e];
+        const int64_t col = col0 + ((int64_t)(e / VEC) * NT + tid) * VEC + (e % VEC);
+        if (col < a.d) out[col] = lost ? __builtin_nanf("") : (float)v[e];
     }
 }
 
@@ -410,6 +450,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     V(64, 8, 8, 1, 8) V(64, 8, 8, 4, 2)                                                        \
     V(256, 8, 8, 1, 8) V(256, 16, 8, 1, 8) V(256, 32, 8, 1, 4) V(256, 32, 8, 4, 2)             \
     V(256, 8, 8, 4, 2) V(256, 16, 8, 4, 2)                                                     \
+    V(256, 8, 8, 2, 4) V(256, 16, 8, 2, 4) V(256, 32, 8, 2, 4) V(256, 64, 8, 2, 2) V(256, 64, 8, 1, 4) \
+    V(256, 64, 8, 4, 2)                                                                        \
     V(256, 8, 8, 1, -2) V(256, 16, 8, 1, -2) V(256, 32, 8, 1, -2)                              \
     V(256, 8, 8, 2, -2) V(256, 16, 8, 2, -2) V(256, 32, 8, 2, -2)                              \
     V(1024, 16, 8, 1, -1) V(1024, 32, 8, 1, -1) WPSGD_WIDEST_LDS(V, 8)                          \
@@ -421,6 +463,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     V(256, 4, 4, 1, 8) V(256, 8, 4, 1, 8) V(256, 16, 4, 1, 8) V(256, 32, 4, 1, 4) V(256, 16, 4, 1, 16) V(256, 8, 4, 1, 16)             \
     V(256, 4, 4, 4, 2) V(256, 8, 4, 4, 2) V(256, 16, 4, 4, 2) V(256, 16, 4, 1, 4)              \
     V(256, 16, 4, 2, 2) V(256, 16, 4, 2, 4) V(256, 16, 4, 2, 8) V(256, 32, 4, 4, 2)            \
+    V(256, 4, 4, 2, 4) V(256, 8, 4, 2, 4) V(256, 32, 4, 2, 2)                                  \
     V(256, 4, 4, 1, -2) V(256, 8, 4, 1, -2) V(256, 16, 4, 1, -2) V(256, 32, 4, 1, -2)          \
     V(256, 4, 4, 2, -2) V(256, 8, 4, 2, -2) V(256, 16, 4, 2, -2)                               \
     V(512, 8, 4, 1, 8) V(512, 8, 4, 4, 2) V(512, 8, 4, 2, 4)                                   \
@@ -457,7 +500,7 @@ static void launch_variant(const ChainArgs &a, hipStream_t s)
         }
         ChainArgs b = a;
         if (claim == 0) b.helpers = 0;
-        hipLaunchKernelGGL(kernel, dim3(b.k + b.helpers), dim3(NT), claim, s, b);
+        hipLaunchKernelGGL(kernel, dim3(b.k * b.slices + b.helpers), dim3(NT), claim, s, b);
     }
 }
 

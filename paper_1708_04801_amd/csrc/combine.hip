@@ -218,6 +218,20 @@ hipError_t launch_stream_rows(const void *X, int64_t row_stride, uint32_t row_by
     return hipGetLastError();
 }
 
+__global__ void zero_words_kernel(uint32_t *p, size_t words)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// a fill kernel rather than a memset: the call may sit inside a captured graph
+hipError_t launch_zero_words(uint32_t *p, size_t words, hipStream_t s)
+{
+    if (words == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((words + 255) / 256 < 256 ? (words + 255) / 256 : 256);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(grid), dim3(256), 0, s, p, words);
+    return hipGetLastError();
+}
+
 hipError_t launch_sample_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t chain, int64_t n0,
                               int64_t count, uint32_t m, uint32_t shard_k, int64_t *out, hipStream_t s)
 {

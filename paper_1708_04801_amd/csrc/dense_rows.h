@@ -53,6 +53,200 @@ struct RowFrag {
     }
 };
 
+__device__ inline uint32_t xcd_of_this_wave()
+{
+    uint32_t x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    return x & 0xfu;
+}
+
+// ---------------------------------------------------------------------------------------------
+// A chain cut into column slices, one workgroup (and compute unit) per slice: every slice holds
+// its part of the model vector and reads its part of each row, and once per round the slices add
+// up their partial sums.  The sums travel through a small table in global memory, one 128-byte
+// slot per (chain, slice, round parity).  A slot holds up to twelve 32-bit words of sums in up to
+// four 16-byte records {w0, w1, w2, stamp}, each followed 64 bytes later by its mirror image
+// {stamp, w2, w1, w0}; stamp = round number + 1 (the table is zero at launch).  A reader accepts a
+// slot when every record and its mirror carry the stamp it waits for and agree word for word, so
+// it never uses half of one round's record and half of another's.  The same parity's slot is
+// written again only two rounds later, after its writer has read every slice's record of the
+// round in between, which those slices published after reading this one: nobody still reads a
+// slot when it is overwritten.  Every wait has a budget; a slice that loses the others fills its
+// part of the result with NaN and ends.
+//
+// NEAR: all slices of the chain run on one XCD and meet in its L2: plain stores end up there, and
+// device-scope loads skip the reader's own first-level cache and find them (measured between two
+// compute units of one XCD: 580 cycles one way, against 1000-1200 with device-scope stores, which
+// are what slices on different XCDs need; loads of narrower scope are served from the reader's
+// own first-level cache and never see the other side's store).
+// ---------------------------------------------------------------------------------------------
+constexpr int kMaxSlices = 8;
+constexpr int kSliceSlotWords = 32;
+constexpr int kSliceMaxWords = 12;
+
+__device__ inline uint32_t *slice_slot(const ChainArgs &a, int chain_block, int slice, int parity)
+{
+    return static_cast<uint32_t *>(a.xchg) + (((size_t)chain_block * kMaxSlices + slice) * 2 + parity) * kSliceSlotWords;
+}
+
+template <bool NEAR, int NWORDS>
+__device__ inline void slice_publish(uint32_t *slot, const uint32_t (&w)[kSliceMaxWords], uint32_t stamp)
+{
+#pragma unroll
+    for (int q = 0; q < (NWORDS + 2) / 3; ++q) {
+        u32x4 rec, mirror;
+        rec[0] = w[3 * q]; rec[1] = w[3 * q + 1]; rec[2] = w[3 * q + 2]; rec[3] = stamp;
+        mirror[0] = stamp; mirror[1] = w[3 * q + 2]; mirror[2] = w[3 * q + 1]; mirror[3] = w[3 * q];
+        uint32_t *at = slot + 4 * q;
+        if constexpr (NEAR) {
+            asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:64"
+                         :
+                         : "v"(at), "v"(rec), "v"(mirror)
+                         : "memory");
+        } else {
+            asm volatile("global_store_dwordx4 %0, %1, off sc1\n\tglobal_store_dwordx4 %0, %2, off offset:64 sc1"
+                         :
+                         : "v"(at), "v"(rec), "v"(mirror)
+                         : "memory");
+        }
+    }
+}
+
+// the slot's words if it is complete for `stamp` (the loads are waited for inside: their results are
+// ordinary registers afterwards)
+// the slot's words if it is complete for `stamp`.  All loads and the wait for them sit in one
+// assembly statement: their results are ordinary registers when it ends.
+template <int NWORDS>
+__device__ inline bool slice_read(const uint32_t *slot, uint32_t stamp, uint32_t (&w)[kSliceMaxWords])
+{
+    constexpr int NQ = (NWORDS + 2) / 3;
+    static_assert(NQ >= 1 && NQ <= 4, "one to four records");
+    u32x4 rec[NQ], mirror[NQ];
+    if constexpr (NQ == 1) {
+        asm volatile("global_load_dwordx4 %0, %2, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %2, off offset:64 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(rec[0]), "=&v"(mirror[0])
+                     : "v"(slot)
+                     : "memory");
+    } else if constexpr (NQ == 2) {
+        asm volatile("global_load_dwordx4 %0, %4, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %4, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %2, %4, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %3, %4, off offset:80 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(rec[0]), "=&v"(mirror[0]), "=&v"(rec[1]), "=&v"(mirror[1])
+                     : "v"(slot)
+                     : "memory");
+    } else if constexpr (NQ == 3) {
+        asm volatile("global_load_dwordx4 %0, %6, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %6, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %2, %6, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %3, %6, off offset:80 sc1\n\t"
+                     "global_load_dwordx4 %4, %6, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %5, %6, off offset:96 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(rec[0]), "=&v"(mirror[0]), "=&v"(rec[1]), "=&v"(mirror[1]), "=&v"(rec[2]), "=&v"(mirror[2])
+                     : "v"(slot)
+                     : "memory");
+    } else {
+        asm volatile("global_load_dwordx4 %0, %8, off offset:0 sc1\n\t"
+                     "global_load_dwordx4 %1, %8, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %2, %8, off offset:16 sc1\n\t"
+                     "global_load_dwordx4 %3, %8, off offset:80 sc1\n\t"
+                     "global_load_dwordx4 %4, %8, off offset:32 sc1\n\t"
+                     "global_load_dwordx4 %5, %8, off offset:96 sc1\n\t"
+                     "global_load_dwordx4 %6, %8, off offset:48 sc1\n\t"
+                     "global_load_dwordx4 %7, %8, off offset:112 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(rec[0]), "=&v"(mirror[0]), "=&v"(rec[1]), "=&v"(mirror[1]), "=&v"(rec[2]), "=&v"(mirror[2]), "=&v"(rec[3]), "=&v"(mirror[3])
+                     : "v"(slot)
+                     : "memory");
+    }
+    bool ok = true;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        ok = ok && rec[q][3] == stamp && mirror[q][0] == stamp && rec[q][0] == mirror[q][3] && rec[q][1] == mirror[q][2] &&
+             rec[q][2] == mirror[q][1];
+        w[3 * q] = rec[q][0];
+        w[3 * q + 1] = rec[q][1];
+        w[3 * q + 2] = rec[q][2];
+    }
+    return ok;
+}
+
+// Do all slices of this chain run on one XCD?  Every slice writes its XCD number (plus one) behind
+// the slots, at device scope, and reads the others'; if they do not all show up in time the answer
+// is no, which is always safe.
+__device__ inline bool slices_share_an_xcd(const ChainArgs &a, int chain_block, int slice, bool announcer)
+{
+    uint32_t *words = static_cast<uint32_t *>(a.xchg) + (size_t)a.k * kMaxSlices * 2 * kSliceSlotWords +
+                      (size_t)chain_block * kMaxSlices;
+    const uint32_t mine = xcd_of_this_wave() + 1u;
+    if (announcer) __hip_atomic_store(words + slice, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int lane = (int)(threadIdx.x & (kWave - 1));
+    bool all = false, same = false;
+    for (int tries = 0; tries < (1 << 14) && !all; ++tries) {
+        const uint32_t x = lane < a.slices ? __hip_atomic_load(words + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : mine;
+        all = __builtin_amdgcn_ballot_w64(x != 0u) == ~0ull;
+        same = __builtin_amdgcn_ballot_w64(x == mine) == ~0ull;
+        if (!all) __builtin_amdgcn_s_sleep(8);
+    }
+    return all && same;
+}
+
+// Adds the slices' sums for this round, in slice order.  w holds NVAL values of this slice (fp32:
+// one word each; fp64: two), identical in every wave of the slice; lane 0 of wave 0 publishes them.
+// Returns false if the other slices did not show up.
+template <bool IS_F64, int NVAL, bool NEAR>
+__device__ inline bool slices_all_reduce(const ChainArgs &a, int chain_block, int slice, bool publisher, uint32_t round,
+                                         uint32_t (&w)[kSliceMaxWords])
+{
+    constexpr int NWORDS = IS_F64 ? 2 * NVAL : NVAL;
+    static_assert(NWORDS <= kSliceMaxWords, "a slot holds twelve words");
+    const int lane = (int)(threadIdx.x & (kWave - 1));
+    const int parity = (int)(round & 1u);
+    const uint32_t stamp = round + 1u;
+    if (publisher) slice_publish<NEAR, NWORDS>(slice_slot(a, chain_block, slice, parity), w, stamp);
+    const int src = lane < a.slices ? lane : 0;                   // lanes beyond the slices repeat slice 0
+    const uint32_t *slot = slice_slot(a, chain_block, src, parity);
+    uint32_t got[kSliceMaxWords];
+    bool all = false;
+    for (int tries = 0; tries < (1 << 17) && !all; ++tries)
+        all = __builtin_amdgcn_ballot_w64(slice_read<NWORDS>(slot, stamp, got)) == ~0ull;
+    if (!all) return false;
+    if constexpr (IS_F64) {
+        double t[NVAL];
+#pragma unroll
+        for (int r = 0; r < NVAL; ++r) t[r] = 0.0;
+        for (int s = 0; s < a.slices; ++s) {
+#pragma unroll
+            for (int r = 0; r < NVAL; ++r) {
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)got[2 * r], s);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)got[2 * r + 1], s);
+                t[r] += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < NVAL; ++r) {
+            const uint64_t bits = (uint64_t)__double_as_longlong(t[r]);
+            w[2 * r] = (uint32_t)bits;
+            w[2 * r + 1] = (uint32_t)(bits >> 32);
+        }
+    } else {
+        float t[NVAL];
+#pragma unroll
+        for (int r = 0; r < NVAL; ++r) t[r] = 0.0f;
+        for (int s = 0; s < a.slices; ++s) {
+#pragma unroll
+            for (int r = 0; r < NVAL; ++r) t[r] += __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)got[r], s));
+        }
+#pragma unroll
+        for (int r = 0; r < NVAL; ++r) w[r] = __float_as_uint(t[r]);
+    }
+    return true;
+}
+
 // A helper workgroup (one whose index is k or more) runs ahead of a chain and touches one dword
 // of every 128-byte line of the rows the chain will visit, so that they sit in the L2 cache of the
 // chain's XCD when the chain asks for them.  One compute unit draws some 55-60 GB/s from HBM however
@@ -76,13 +270,6 @@ struct RowFrag {
 constexpr int kLeadMin = 10, kLeadMax = 26;
 constexpr uint32_t kChainDone = 0xFFFFFFFFu;      // published by a chain that has finished
 constexpr int kMaxXcds = 16;
-
-__device__ inline uint32_t xcd_of_this_wave()
-{
-    uint32_t x;
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
-    return x & 0xfu;
-}
 
 // called by thread 0 of a chain workgroup before its first step.  Helpers on every XCD read this
 // word and each XCD has an L2 cache of its own, so it is stored at device scope (written through);

@@ -41,6 +41,10 @@ struct ChainArgs {
     int helpers;
     uint32_t *progress;       // DEVICE, 2k+16 entries, zero at launch: [b] steps workgroup b has completed
                               // (low 32 bits), [k+b] its XCD number plus one, [2k+x] helper seats taken on XCD x
+    // Column slices (dense register kernel): workgroup b + s*k runs slice s of the chain of workgroup b;
+    // xchg is the table the slices add their partial sums through (zero at launch), else unused.
+    int slices;               // 1: a chain is one workgroup
+    void *xchg;               // DEVICE, k * 8 * 2 slots of 128 bytes, then k * 8 words (the slices' XCD numbers)
     // outputs / scratch
     float *W;                 // k x d
     void *state;              // k x d model vectors in HBM (state_in_hbm plans), else unused
@@ -60,6 +64,7 @@ struct Plan {
     int prefetch;    // P: rounds in flight
     int rows;        // DenseReg: 1 rows wait in registers, 2 next row staged in LDS, 3 rows streamed twice,
                      // 4 rows fed through an LDS ring by mover waves
+    int slices;      // DenseReg, rows = 1: workgroups (column slices) per chain
     size_t state_bytes_per_elem;   // 0 when the state lives in registers
 };
 
@@ -70,6 +75,7 @@ hipError_t launch_csr(const Plan &p, const ChainArgs &a, hipStream_t s);
 hipError_t launch_csr_pair(const Plan &p, const ChainArgs &a, hipStream_t s);   // two waves per chain
 bool dense_reg_has(const Plan &p);   // is (dtype, loss, threads, ept, vec, B, P) instantiated?
 
+hipError_t launch_zero_words(uint32_t *p, size_t words, hipStream_t s);
 hipError_t launch_combine(const float *W, const double *a_dev, int k, int64_t d, float *w_out,
                           hipStream_t s);
 hipError_t launch_stream_rows(const void *X, int64_t row_stride, uint32_t row_bytes, uint32_t m,

@@ -185,6 +185,39 @@ def test_dense_chains_with_helper_workgroups(k, d, helpers, extra, loss):
     check_against_oracle(w, W, label=f"helped k={k} d={d} [{desc}]")
 
 
+@pytest.mark.parametrize("d,bf16,loss,plan", [
+    (4096, False, wl.LOGISTIC, {"slices": 2}), (4096, False, wl.LOGISTIC, {"slices": 4}),
+    (4096, False, wl.LOGISTIC, {"slices": 2, "block_steps": 1}), (4096, False, wl.HINGE, {"slices": 2}),
+    (4096, False, wl.HINGE, {"slices": 4}), (3000, False, wl.LOGISTIC, {"slices": 3}),
+    (8192, False, wl.LOGISTIC, {"slices": 8}), (5000, False, wl.HINGE, {"slices": 5}),
+    (4096, True, wl.LOGISTIC, {"slices": 2}), (16384, True, wl.HINGE, {"slices": 4}),
+    (65536, True, wl.LOGISTIC, {"slices": 4}), (65536, True, wl.LOGISTIC, {"slices": 8}),
+    (4096, False, wl.LOGISTIC, {"slices": 2, "block_steps": 4}), (4096, False, wl.HINGE, {"slices": 4, "block_steps": 2}),
+    (65536, True, wl.LOGISTIC, {"slices": 8, "block_steps": 4}), (65536, True, wl.LOGISTIC, {"slices": 4, "block_steps": 4}),
+    (16384, True, wl.HINGE, {"slices": 2, "block_steps": 2})])
+def test_dense_chains_cut_into_column_slices(d, bf16, loss, plan):
+    """A chain spread over several compute units, each with a slice of the columns; the slices add
+    their partial sums through global memory once per round."""
+    rng = np.random.default_rng(d + 11 * loss + plan["slices"])
+    m, k = 160, 6
+    Xf = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    n = np.array([257, 64, 0, 1, 130, 63], dtype=np.int64)
+    if bf16:
+        bits = wl.f32_to_bf16_bits(Xf)
+        y = np.where(wl.bf16_bits_to_f32(bits) @ rng.standard_normal(d) >= 0, 1.0, -1.0).astype(np.float32)
+        w = wl.Workload("sliced_bf16", loss, 0.5, 1e-3, 13, n, y, m, d, dense=bits)
+    else:
+        y = np.where(Xf @ rng.standard_normal(d) + 0.3 * rng.standard_normal(m) >= 0, 1.0, -1.0).astype(np.float32)
+        w = wl.Workload("sliced", loss, 0.5 if loss == wl.HINGE else 2.0, 1e-3, 13, n, y, m, d, dense=Xf)
+    Xg = api.matrix_from_workload(w)
+    desc = api.wpsgd_describe_plan(Xg, k, loss, plan)
+    assert f"slices={plan['slices']}" in desc
+    W = gpu_chains(w, plan=plan, X=Xg)
+    check_against_oracle(w, W, label=f"sliced d={d} [{desc}]")
+    assert (W[2] == 0).all()
+    assert torch.equal(W, gpu_chains(w, plan=plan, X=Xg))            # same inputs, same bits
+
+
 BF16_PLANS = [(64, None), (256, None), (512, None), (520, None), (2048, {"block_steps": 4}), (4096, None),
               (8192, {"block_steps": 1}), (16384, None), (30000, None), (65536, None),
               (65536, {"state_in_hbm": 1}), (4100, {"state_in_hbm": 1}), (40000, None), (33000, None),
@@ -210,8 +243,9 @@ def test_dense_bf16_chains(d, plan, loss):
 
 
 def test_widest_bf16_rows_both_ways():
-    """d = 65536 in bfloat16 (128 KiB rows): the LDS-staged kernel is the default, the kernel that
-    streams every row twice stays reachable; both must match the oracle and each other closely."""
+    """d = 65536 in bfloat16 (128 KiB rows): few chains are cut into column slices, one workgroup per
+    chain means the LDS-staged kernel, the kernel that streams every row twice stays reachable; all
+    must match the oracle."""
     rng = np.random.default_rng(77)
     m, d = 80, 65536
     bits = wl.f32_to_bf16_bits((rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32))
@@ -219,9 +253,11 @@ def test_widest_bf16_rows_both_ways():
     n = np.array([200, 65, 1, 0, 64], dtype=np.int64)
     w = wl.Workload("bf16_widest", wl.LOGISTIC, 0.5, 1e-3, 5, n, y, m, d, dense=bits)
     Xg = api.matrix_from_workload(w)
-    assert "rows=lds" in api.wpsgd_describe_plan(Xg, 5, wl.LOGISTIC)
+    assert "slices=8" in api.wpsgd_describe_plan(Xg, 5, wl.LOGISTIC)                 # few chains: eight compute units each
+    assert "rows=lds" in api.wpsgd_describe_plan(Xg, 5, wl.LOGISTIC, {"slices": 1})
+    assert "rows=lds" in api.wpsgd_describe_plan(Xg, 200, wl.LOGISTIC)               # no compute units to spare
     assert "rows=twice" in api.wpsgd_describe_plan(Xg, 5, wl.LOGISTIC, {"rows": 3})
-    for plan in (None, {"rows": 3}):
+    for plan in (None, {"slices": 1}, {"rows": 3}):
         W = gpu_chains(w, plan=plan, X=Xg)
         check_against_oracle(w, W, label=f"bf16 widest {plan}")
         assert torch.equal(W, gpu_chains(w, plan=plan, X=Xg))
