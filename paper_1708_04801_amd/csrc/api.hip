@@ -157,6 +157,7 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
                     // the slices' exchange carries twelve words: ten fp32 sums (4 steps per round) or three fp64 sums (2 steps)
                     q.rows = 1;
                     if (f.rows > 1 || vec == 1 || k * slices > compute_units()) continue;
+                    if ((size_t)X->d * state_elem < 2304) continue;       // the exchange table borrows the HBM-state area: 2080 bytes a chain
                     if (!q.block_steps) q.block_steps = p.loss == WPSGD_LOGISTIC ? 2 : 1;
                     if (q.block_steps > (p.loss == WPSGD_LOGISTIC ? 4 : 2)) continue;
                 }
