@@ -89,8 +89,10 @@ typedef struct wpsgd_plan {
     int slices;          /* dense, 256 threads, rows in registers: compute units per chain.  Each takes a
                             slice of 256 x (elements per thread) columns of the model vector and of every
                             row; the slices add their partial sums through global memory once per round
-                            (logistic: 1 or 2 steps per round; hinge: 1).  0: choose; 1: a chain is one
-                            workgroup; 2..8: that many, which must be what the shape needs to cover d     */
+                            (logistic: up to 4 steps per round; hinge: up to 2).  k*slices must not exceed
+                            the compute units.  0: choose (logistic chains whose rows need more than 256
+                            threads, compute units permitting); 1: a chain is one workgroup; 2..8: that
+                            many, which must be what some 256-thread shape needs to cover d             */
 } wpsgd_plan;
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----
