@@ -90,7 +90,7 @@ typedef struct wpsgd_plan {
                             slice of 256 x (elements per thread) columns of the model vector and of every
                             row; the slices add their partial sums through global memory once per round
                             (logistic: up to 4 steps per round; hinge: up to 2).  k*slices must not exceed
-                            the compute units.  0: choose (logistic chains whose rows need more than 256
+                            the compute units.  0: choose (chains whose rows need more than 256
                             threads, compute units permitting); 1: a chain is one workgroup; 2..8: that
                             many, which must be what some 256-thread shape needs to cover d             */
 } wpsgd_plan;

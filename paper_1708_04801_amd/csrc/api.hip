@@ -158,7 +158,7 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
                     q.rows = 1;
                     if (f.rows > 1 || vec == 1 || k * slices > compute_units()) continue;
                     if ((size_t)X->d * state_elem < 2304) continue;       // the exchange table borrows the HBM-state area: 2080 bytes a chain
-                    if (!q.block_steps) q.block_steps = p.loss == WPSGD_LOGISTIC ? 2 : 1;
+                    if (!q.block_steps) q.block_steps = 2;             // one exchange per two steps
                     if (q.block_steps > (p.loss == WPSGD_LOGISTIC ? 4 : 2)) continue;
                 }
                 // Few chains of 16 KiB fp32 rows, each alone on a compute unit, are bound by the
@@ -188,10 +188,7 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
             // Rows too long for 256 threads, few chains: rather than one chain per 1024-thread workgroup,
             // cut each chain into as many column slices as there are compute units for (the widest
             // workload: 8 slices of 8192 columns run 2.7 times as fast as one workgroup of 1024).
-            // (Logistic chains only: with the hinge's fp64 sums a round is one step, and an exchange per
-            // step costs more than the slices save: 10.1 against 9.4 ms at d = 16384.)
-            if (f.slices == 0 && !f.threads && !f.block_steps && !f.prefetch && !f.rows && found.threads == 1024 &&
-                p.loss == WPSGD_LOGISTIC) {
+            if (f.slices == 0 && !f.threads && !f.block_steps && !f.prefetch && !f.rows && found.threads == 1024) {
                 for (int c = 8; c >= 2; c /= 2) {
                     Plan cut;
                     if (k * c <= compute_units() && search(c, &cut)) {
