@@ -24,6 +24,10 @@
 // Rows are fetched with raw buffer loads: the row's address sits in a scalar descriptor, each
 // lane adds a fixed 32-bit offset, and lanes past the end of the row read zeros.
 //
+// Two things reach beyond the one workgroup (both in dense_rows.h): helper workgroups that run
+// ahead of a chain and pull its rows into L2, and column slices - a chain whose rows are too long
+// for one workgroup runs as several, each with NT*EPT columns, that add their sums once per round.
+//
 // This file is compiled once per (row storage, loss) pair; WPSGD_TX_BF16 and WPSGD_LOSS select it.
 #include "dense_rows.h"
 #include "chain_dense_wide.h"
