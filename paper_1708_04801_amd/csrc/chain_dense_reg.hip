@@ -271,7 +271,11 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 for (int r = 0; r < NR; ++r)
 #pragma unroll
                     for (int w = 0; w < NW; ++w) part[r][w] = red[parity][r][w];
-                if constexpr (P > 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
+                // (A sliced chain requests its rows after the slices' exchange instead: loads return
+                // in order, so the exchange's polls would wait behind rows just requested from HBM.)
+                if constexpr (P > 1) {
+                    if (a.slices == 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
+                }
 #pragma unroll
                 for (int r = 0; r < NR; ++r) {
                     TV t = part[r][0];
@@ -308,6 +312,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     const bool met = near_slices ? slices_all_reduce<sizeof(TV) == 8, NR, true>(a, cb, slice, tid == 0, round_no, w)
                                                  : slices_all_reduce<sizeof(TV) == 8, NR, false>(a, cb, slice, tid == 0, round_no, w);
                     if (!met) lost = true;
+                    if constexpr (P > 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
 #pragma unroll
                     for (int r = 0; r < NR; ++r) {
                         if constexpr (sizeof(TV) == 8) {
