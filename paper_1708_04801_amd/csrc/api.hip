@@ -184,19 +184,22 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
         return false;
         };
         Plan found;
-        if (search(f.slices > 1 ? f.slices : 1, &found)) {
-            // Rows too long for 256 threads, few chains: rather than one chain per 1024-thread workgroup,
-            // cut each chain into as many column slices as there are compute units for (the widest
-            // workload: 8 slices of 8192 columns run 2.7 times as fast as one workgroup of 1024).
-            if (f.slices == 0 && !f.threads && !f.block_steps && !f.prefetch && !f.rows && found.threads == 1024) {
-                for (int c = 8; c >= 2; c /= 2) {
-                    Plan cut;
-                    if (k * c <= compute_units() && search(c, &cut)) {
-                        found = cut;
-                        break;
-                    }
+        bool have = search(f.slices > 1 ? f.slices : 1, &found);
+        // Rows too long for 256 threads (or for any one workgroup), few chains: rather than one chain
+        // per 1024-thread workgroup, cut each chain into as many column slices as there are compute
+        // units for (the widest workload: 8 slices of 8192 columns run 3 times as fast as one
+        // workgroup of 1024; with fp64 state that row length has no one-workgroup shape at all).
+        if (f.slices == 0 && !f.threads && !f.block_steps && !f.prefetch && !f.rows && (!have || found.threads == 1024)) {
+            for (int c = 8; c >= 2; --c) {
+                Plan cut;
+                if (k * c <= compute_units() && search(c, &cut)) {
+                    found = cut;
+                    have = true;
+                    break;
                 }
             }
+        }
+        if (have) {
             *out = found;
             return WPSGD_OK;
         }

@@ -63,16 +63,23 @@ __device__ inline uint32_t xcd_of_this_wave()
 // ---------------------------------------------------------------------------------------------
 // A chain cut into column slices, one workgroup (and compute unit) per slice: every slice holds
 // its part of the model vector and reads its part of each row, and once per round the slices add
-// up their partial sums.  The sums travel through a small table in global memory, one 128-byte
-// slot per (chain, slice, round parity).  A slot holds up to twelve 32-bit words of sums in up to
-// four 16-byte records {w0, w1, w2, stamp}, each followed 64 bytes later by its mirror image
-// {stamp, w2, w1, w0}; stamp = round number + 1 (the table is zero at launch).  A reader accepts a
-// slot when every record and its mirror carry the stamp it waits for and agree word for word, so
-// it never uses half of one round's record and half of another's.  The same parity's slot is
-// written again only two rounds later, after its writer has read every slice's record of the
-// round in between, which those slices published after reading this one: nobody still reads a
-// slot when it is overwritten.  Every wait has a budget; a slice that loses the others fills its
-// part of the result with NaN and ends.
+// up their partial sums.  The sums travel through a small table in global memory, 2 KiB per chain:
+// for each round parity up to four record blocks of 256 bytes.  The first 128-byte line of a block
+// holds one 16-byte record {w0, w1, w2, stamp} per slice, the second line each record's mirror
+// image {stamp, w2, w1, w0}; stamp = round number + 1 (the table is zero at launch), and twelve
+// 32-bit words of sums fit in the four blocks.  Lane s of every wave reads slice s's records, so one
+// poll of a wave touches two lines per block.  A reader accepts a slice's records when each and its
+// mirror carry the stamp it waits for and agree word for word, so it never uses half of one
+// round's record and half of another's.  The same parity's records are written again only two
+// rounds later, after their writer has read every slice's record of the round in between, which
+// those slices published after reading this one: nobody still reads a record when it is
+// overwritten.  Every wait has a budget; a slice that loses the others fills its part of the
+// result with NaN and ends.
+//
+// The accepted sums sit in lanes 0..7 (zero beyond the last slice) and are added by three
+// exchange levels among those lanes: one fixed tree, the same in every wave of every slice, so all
+// slices continue with identical bits.  (Reading them lane by lane into scalars and adding in
+// slice order cost a seventh of the whole pass on the widest workload.)
 //
 // NEAR: all slices of the chain run on one XCD and meet in its L2: plain stores end up there, and
 // device-scope loads skip the reader's own first-level cache and find them (measured between two
@@ -86,7 +93,7 @@ constexpr int kSliceMaxWords = 12;
 
 __device__ inline uint32_t *slice_slot(const ChainArgs &a, int chain_block, int slice, int parity)
 {
-    return static_cast<uint32_t *>(a.xchg) + (((size_t)chain_block * kMaxSlices + slice) * 2 + parity) * kSliceSlotWords;
+    return static_cast<uint32_t *>(a.xchg) + (size_t)chain_block * (kMaxSlices * 2 * kSliceSlotWords) + parity * (4 * 64) + slice * 4;
 }
 
 template <bool NEAR, int NWORDS>
@@ -97,14 +104,14 @@ __device__ inline void slice_publish(uint32_t *slot, const uint32_t (&w)[kSliceM
         u32x4 rec, mirror;
         rec[0] = w[3 * q]; rec[1] = w[3 * q + 1]; rec[2] = w[3 * q + 2]; rec[3] = stamp;
         mirror[0] = stamp; mirror[1] = w[3 * q + 2]; mirror[2] = w[3 * q + 1]; mirror[3] = w[3 * q];
-        uint32_t *at = slot + 4 * q;
+        uint32_t *at = slot + 64 * q;
         if constexpr (NEAR) {
-            asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:64"
+            asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:128"
                          :
                          : "v"(at), "v"(rec), "v"(mirror)
                          : "memory");
         } else {
-            asm volatile("global_store_dwordx4 %0, %1, off sc1\n\tglobal_store_dwordx4 %0, %2, off offset:64 sc1"
+            asm volatile("global_store_dwordx4 %0, %1, off sc1\n\tglobal_store_dwordx4 %0, %2, off offset:128 sc1"
                          :
                          : "v"(at), "v"(rec), "v"(mirror)
                          : "memory");
@@ -112,10 +119,8 @@ __device__ inline void slice_publish(uint32_t *slot, const uint32_t (&w)[kSliceM
     }
 }
 
-// the slot's words if it is complete for `stamp` (the loads are waited for inside: their results are
-// ordinary registers afterwards)
-// the slot's words if it is complete for `stamp`.  All loads and the wait for them sit in one
-// assembly statement: their results are ordinary registers when it ends.
+// One slice's words if its records are complete for `stamp`.  All loads and the wait for them sit
+// in one assembly statement: their results are ordinary registers when it ends.
 template <int NWORDS>
 __device__ inline bool slice_read(const uint32_t *slot, uint32_t stamp, uint32_t (&w)[kSliceMaxWords])
 {
@@ -124,40 +129,40 @@ __device__ inline bool slice_read(const uint32_t *slot, uint32_t stamp, uint32_t
     u32x4 rec[NQ], mirror[NQ];
     if constexpr (NQ == 1) {
         asm volatile("global_load_dwordx4 %0, %2, off offset:0 sc1\n\t"
-                     "global_load_dwordx4 %1, %2, off offset:64 sc1\n\t"
+                     "global_load_dwordx4 %1, %2, off offset:128 sc1\n\t"
                      "s_waitcnt vmcnt(0)"
                      : "=&v"(rec[0]), "=&v"(mirror[0])
                      : "v"(slot)
                      : "memory");
     } else if constexpr (NQ == 2) {
         asm volatile("global_load_dwordx4 %0, %4, off offset:0 sc1\n\t"
-                     "global_load_dwordx4 %1, %4, off offset:64 sc1\n\t"
-                     "global_load_dwordx4 %2, %4, off offset:16 sc1\n\t"
-                     "global_load_dwordx4 %3, %4, off offset:80 sc1\n\t"
+                     "global_load_dwordx4 %1, %4, off offset:128 sc1\n\t"
+                     "global_load_dwordx4 %2, %4, off offset:256 sc1\n\t"
+                     "global_load_dwordx4 %3, %4, off offset:384 sc1\n\t"
                      "s_waitcnt vmcnt(0)"
                      : "=&v"(rec[0]), "=&v"(mirror[0]), "=&v"(rec[1]), "=&v"(mirror[1])
                      : "v"(slot)
                      : "memory");
     } else if constexpr (NQ == 3) {
         asm volatile("global_load_dwordx4 %0, %6, off offset:0 sc1\n\t"
-                     "global_load_dwordx4 %1, %6, off offset:64 sc1\n\t"
-                     "global_load_dwordx4 %2, %6, off offset:16 sc1\n\t"
-                     "global_load_dwordx4 %3, %6, off offset:80 sc1\n\t"
-                     "global_load_dwordx4 %4, %6, off offset:32 sc1\n\t"
-                     "global_load_dwordx4 %5, %6, off offset:96 sc1\n\t"
+                     "global_load_dwordx4 %1, %6, off offset:128 sc1\n\t"
+                     "global_load_dwordx4 %2, %6, off offset:256 sc1\n\t"
+                     "global_load_dwordx4 %3, %6, off offset:384 sc1\n\t"
+                     "global_load_dwordx4 %4, %6, off offset:512 sc1\n\t"
+                     "global_load_dwordx4 %5, %6, off offset:640 sc1\n\t"
                      "s_waitcnt vmcnt(0)"
                      : "=&v"(rec[0]), "=&v"(mirror[0]), "=&v"(rec[1]), "=&v"(mirror[1]), "=&v"(rec[2]), "=&v"(mirror[2])
                      : "v"(slot)
                      : "memory");
     } else {
         asm volatile("global_load_dwordx4 %0, %8, off offset:0 sc1\n\t"
-                     "global_load_dwordx4 %1, %8, off offset:64 sc1\n\t"
-                     "global_load_dwordx4 %2, %8, off offset:16 sc1\n\t"
-                     "global_load_dwordx4 %3, %8, off offset:80 sc1\n\t"
-                     "global_load_dwordx4 %4, %8, off offset:32 sc1\n\t"
-                     "global_load_dwordx4 %5, %8, off offset:96 sc1\n\t"
-                     "global_load_dwordx4 %6, %8, off offset:48 sc1\n\t"
-                     "global_load_dwordx4 %7, %8, off offset:112 sc1\n\t"
+                     "global_load_dwordx4 %1, %8, off offset:128 sc1\n\t"
+                     "global_load_dwordx4 %2, %8, off offset:256 sc1\n\t"
+                     "global_load_dwordx4 %3, %8, off offset:384 sc1\n\t"
+                     "global_load_dwordx4 %4, %8, off offset:512 sc1\n\t"
+                     "global_load_dwordx4 %5, %8, off offset:640 sc1\n\t"
+                     "global_load_dwordx4 %6, %8, off offset:768 sc1\n\t"
+                     "global_load_dwordx4 %7, %8, off offset:896 sc1\n\t"
                      "s_waitcnt vmcnt(0)"
                      : "=&v"(rec[0]), "=&v"(mirror[0]), "=&v"(rec[1]), "=&v"(mirror[1]), "=&v"(rec[2]), "=&v"(mirror[2]), "=&v"(rec[3]), "=&v"(mirror[3])
                      : "v"(slot)
@@ -195,7 +200,22 @@ __device__ inline bool slices_share_an_xcd(const ChainArgs &a, int chain_block, 
     return all && same;
 }
 
-// Adds the slices' sums for this round, in slice order.  w holds NVAL values of this slice (fp32:
+// the value a lane pattern (a DPP control word) brings from another lane of the same row of 16
+template <int CTRL>
+__device__ inline float from_other_lane(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ inline double from_other_lane(double v)
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong(v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)bits, CTRL, 0xf, 0xf, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(bits >> 32), CTRL, 0xf, 0xf, true);
+    return __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+}
+
+// Adds the slices' sums for this round, in one fixed tree.  w holds NVAL values of this slice (fp32:
 // one word each; fp64: two), identical in every wave of the slice; lane 0 of wave 0 publishes them.
 // Returns false if the other slices did not show up.
 template <bool IS_F64, int NVAL, bool NEAR>
@@ -216,33 +236,28 @@ __device__ inline bool slices_all_reduce(const ChainArgs &a, int chain_block, in
         all = __builtin_amdgcn_ballot_w64(slice_read<NWORDS>(slot, stamp, got)) == ~0ull;
     if (!all) return false;
     if constexpr (IS_F64) {
-        double t[NVAL];
-#pragma unroll
-        for (int r = 0; r < NVAL; ++r) t[r] = 0.0;
-        for (int s = 0; s < a.slices; ++s) {
-#pragma unroll
-            for (int r = 0; r < NVAL; ++r) {
-                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)got[2 * r], s);
-                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)got[2 * r + 1], s);
-                t[r] += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
-            }
-        }
+        // as below, on the two halves of each fp64 sum
 #pragma unroll
         for (int r = 0; r < NVAL; ++r) {
-            const uint64_t bits = (uint64_t)__double_as_longlong(t[r]);
-            w[2 * r] = (uint32_t)bits;
-            w[2 * r + 1] = (uint32_t)(bits >> 32);
+            double t = lane < a.slices ? __longlong_as_double((long long)(((uint64_t)got[2 * r + 1] << 32) | got[2 * r])) : 0.0;
+            t += from_other_lane<0xB1>(t);
+            t += from_other_lane<0x4E>(t);
+            t += from_other_lane<0x141>(t);
+            const uint64_t bits = (uint64_t)__double_as_longlong(t);
+            w[2 * r] = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)bits);
+            w[2 * r + 1] = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(bits >> 32));
         }
     } else {
-        float t[NVAL];
+        // lanes 0..7 hold the slices' sums (zero beyond the last slice); three exchange levels among
+        // those eight lanes add them in one fixed tree, the same in every slice and wave
 #pragma unroll
-        for (int r = 0; r < NVAL; ++r) t[r] = 0.0f;
-        for (int s = 0; s < a.slices; ++s) {
-#pragma unroll
-            for (int r = 0; r < NVAL; ++r) t[r] += __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)got[r], s));
+        for (int r = 0; r < NVAL; ++r) {
+            float t = lane < a.slices ? __uint_as_float(got[r]) : 0.0f;
+            t += from_other_lane<0xB1>(t);      // quad_perm [1,0,3,2]
+            t += from_other_lane<0x4E>(t);      // quad_perm [2,3,0,1]
+            t += from_other_lane<0x141>(t);     // row_half_mirror
+            w[r] = (uint32_t)__builtin_amdgcn_readfirstlane(__float_as_int(t));
         }
-#pragma unroll
-        for (int r = 0; r < NVAL; ++r) w[r] = __float_as_uint(t[r]);
     }
     return true;
 }

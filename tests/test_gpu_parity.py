@@ -262,6 +262,14 @@ def test_widest_bf16_rows_both_ways():
         W = gpu_chains(w, plan=plan, X=Xg)
         check_against_oracle(w, W, label=f"bf16 widest {plan}")
         assert torch.equal(W, gpu_chains(w, plan=plan, X=Xg))
+    # fp64 state (hinge) has no one-workgroup register shape at this width: slices, or the HBM-state kernel
+    wh = wl.Workload("bf16_widest_hinge", wl.HINGE, 0.5, 1e-3, 5, n, y, m, d, dense=bits)
+    assert "slices=8" in api.wpsgd_describe_plan(Xg, 5, wl.HINGE)
+    assert "dense_mem" in api.wpsgd_describe_plan(Xg, 200, wl.HINGE)
+    for plan in (None, {"slices": 4}):
+        W = gpu_chains(wh, plan=plan, X=Xg)
+        check_against_oracle(wh, W, label=f"bf16 widest hinge {plan}")
+        assert torch.equal(W, gpu_chains(wh, plan=plan, X=Xg))
 
 
 def test_dense_rows_with_padding_and_misaligned_base():

@@ -132,7 +132,17 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
     assert "helpers" not in d(_FakeMatrix(262144, 4096), 129, api.LOGISTIC)
     assert "helpers" not in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"helpers": -1})
     assert "rows=fed" in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"rows": 4})
-    for bad in ({"helpers": 4}, {"helpers": -2}, {"rows": 5}):
+    # rows too long for one 256-thread workgroup and compute units to spare: column slices
+    assert "ept=32 vec=8 B=2 P=4" in d(_FakeMatrix(65536, 65536, api.BF16), 32, api.LOGISTIC)
+    assert "slices=8" in d(_FakeMatrix(65536, 65536, api.BF16), 32, api.LOGISTIC)
+    assert "ept=64 vec=8 B=2 P=2" in d(_FakeMatrix(65536, 65536, api.BF16), 33, api.LOGISTIC)    # 33 * 8 > 256 compute units:
+    assert "slices=4" in d(_FakeMatrix(65536, 65536, api.BF16), 33, api.LOGISTIC)                # four wider slices
+    assert "rows=lds" in d(_FakeMatrix(65536, 65536, api.BF16), 200, api.LOGISTIC)               # none to spare
+    assert "slices=8" in d(_FakeMatrix(65536, 65536, api.BF16), 32, api.HINGE)          # fp64 state: no one-workgroup shape
+    assert d(_FakeMatrix(65536, 65536, api.BF16), 200, api.HINGE).startswith("dense_mem")
+    assert "slices=5" in d(_FakeMatrix(1000, 40000), 9, api.HINGE)                      # 5 * 8192 columns cover 40000, 4 do not
+    assert "slices" not in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC)
+    for bad in ({"helpers": 4}, {"helpers": -2}, {"rows": 5}, {"slices": 9}, {"slices": -1}):
         with pytest.raises(api.WpsgdError) as err:
             d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan=bad)
         assert err.value.status == api.INVALID_ARG
