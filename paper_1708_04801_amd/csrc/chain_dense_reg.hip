@@ -45,7 +45,10 @@ constexpr int kLoss = WPSGD_LOSS;
 
 // TX and LOSS are template parameters (not just per-file constants) so that the four builds of
 // this file produce four distinct sets of kernel symbols.
-template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P>
+// SLICED: the launch cuts every chain into a.slices column slices (a kernel of its own, so that the
+// one-workgroup chain carries none of the slices' exchange, not even as a branch not taken: the
+// mere presence of that branch between the barrier and the row requests cost 15 % at d = 4096).
+template <typename TX, int LOSS, int NT, int EPT, int VEC, int B, int P, bool SLICED>
 __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 {
     using TV = typename StateType<LOSS>::type;     // state, dot products and the step recursion
@@ -60,18 +63,22 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     // Labels of a whole window, gathered straight into LDS one window ahead (per wave, two windows)
     __shared__ float ylab[NW][2][kWave];
 
-    if ((int)blockIdx.x >= a.k * a.slices) {       // a helper workgroup: see run_ahead_of_chain
-        run_ahead_of_chain<TX>(a, reinterpret_cast<uint32_t *>(&ylab[0][0][0]));
-        return;
+    if constexpr (!SLICED) {
+        if ((int)blockIdx.x >= a.k) {              // a helper workgroup: see run_ahead_of_chain
+            run_ahead_of_chain<TX>(a, reinterpret_cast<uint32_t *>(&ylab[0][0][0]));
+            return;
+        }
     }
     const int tid = threadIdx.x;
-    if (a.helpers > 0 && tid == 0) announce_chain_workgroup(a);
+    if constexpr (!SLICED) {
+        if (a.helpers > 0 && tid == 0) announce_chain_workgroup(a);
+    }
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     // Workgroup cb + s*k runs column slice s of the chain of workgroup cb: columns
     // [s*NT*EPT, (s+1)*NT*EPT) of the model vector and of every row.  One slice is the whole chain.
-    const int cb = a.slices > 1 ? (int)(blockIdx.x % (unsigned)a.k) : (int)blockIdx.x;
-    const int slice = a.slices > 1 ? (int)(blockIdx.x / (unsigned)a.k) : 0;
+    const int cb = SLICED ? (int)(blockIdx.x % (unsigned)a.k) : (int)blockIdx.x;
+    const int slice = SLICED ? (int)(blockIdx.x / (unsigned)a.k) : 0;
     const int64_t col0 = (int64_t)slice * (NT * EPT);
     const int chain = a.order[cb];
     const int64_t n = a.nsteps[cb];
@@ -209,7 +216,8 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         request_labels(1, rows_b);
 
         uint32_t round_no = 0;              // rounds done, as the slices of a chain count them
-        const bool near_slices = a.slices > 1 && slices_share_an_xcd(a, cb, slice, tid == 0);
+        bool near_slices = false;
+        if constexpr (SLICED) near_slices = slices_share_an_xcd(a, cb, slice, tid == 0);
         int parity = 0;
         // One round: steps at in-window positions j .. j+B-1, rows in slot u.  While the partial
         // sums cross the workgroup, slot u_prev (consumed one round ago) is requested again for
@@ -273,9 +281,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     for (int w = 0; w < NW; ++w) part[r][w] = red[parity][r][w];
                 // (A sliced chain requests its rows after the slices' exchange instead: loads return
                 // in order, so the exchange's polls would wait behind rows just requested from HBM.)
-                if constexpr (P > 1) {
-                    if (a.slices == 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
-                }
+                if constexpr (P > 1 && !SLICED) issue_rows(u_prev, next_rows, 0, kFirstHalf);
 #pragma unroll
                 for (int r = 0; r < NR; ++r) {
                     TV t = part[r][0];
@@ -294,8 +300,9 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                 }
             }
             // several slices: add up the slices' sums (every wave of every slice ends with the same totals)
-            if constexpr (NW > 1 && NR * sizeof(TV) <= kSliceMaxWords * 4) {
-                if (a.slices > 1) {
+            static_assert(!SLICED || (NW > 1 && NR * sizeof(TV) <= kSliceMaxWords * 4), "the slices' exchange carries twelve words");
+            if constexpr (SLICED) {
+                {
                     uint32_t w[kSliceMaxWords];
 #pragma unroll
                     for (int q = 0; q < kSliceMaxWords; ++q) w[q] = 0u;
@@ -380,7 +387,9 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         const int64_t ngroups = (nblk + P - 1) / P;
         int j0 = 0;                                 // in-window position of the group's first step
         for (int64_t g = 0; g < ngroups; ++g) {
-            if (a.helpers > 0 && tid == 0) a.progress[cb] = (uint32_t)(g * D);   // for the helpers to see
+            if constexpr (!SLICED) {
+                if (a.helpers > 0 && tid == 0) a.progress[cb] = (uint32_t)(g * D);   // for the helpers to see
+            }
             if (j0 == 0) {      // a new window of 64 steps begins (never in the middle of a group)
                 const int64_t w = (g * D) / kWave;
                 if (w > 0) {
@@ -415,7 +424,9 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
             if (lost) break;                        // (uniform within a wave)
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);      // no label load may still be on its way to LDS when the wave ends
-        if (a.helpers > 0 && tid == 0) a.progress[cb] = kChainDone;
+        if constexpr (!SLICED) {
+            if (a.helpers > 0 && tid == 0) a.progress[cb] = kChainDone;
+        }
         // scale at the chain's end: s_w covers the steps before the last window
         const int64_t last_w = (n - 1) / kWave;
         const int rem = (int)(n - last_w * kWave);                          // 1..64 steps in it
@@ -484,6 +495,14 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 
 #define WPSGD_ALL_VARIANTS(V) WPSGD_VARIANTS_VEC(V) WPSGD_VARIANTS_ANY(V) WPSGD_VARIANTS_WIDE(V)
 
+// Which variants also exist as a kernel for column slices: four waves, vector loads, rows in
+// registers, and sums that fit the slices' records (twelve 32-bit words).
+constexpr bool can_slice(int nt, int vec, int bb, int pp)
+{
+    return nt == 256 && vec > 1 && pp > 0 &&
+           (bb + bb * (bb - 1) / 2) * sizeof(typename StateType<kLoss>::type) <= (size_t)kSliceMaxWords * 4;
+}
+
 template <int NT, int EPT, int VEC, int BB, int PP>
 static void launch_variant(const ChainArgs &a, hipStream_t s)
 {
@@ -495,7 +514,13 @@ static void launch_variant(const ChainArgs &a, hipStream_t s)
     } else if constexpr (PP == 0) {
         hipLaunchKernelGGL((chain_dense_wide_kernel<RowElem, kLoss, NT, EPT, VEC>), dim3(a.k), dim3(NT), 0, s, a);
     } else {
-        auto kernel = chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP>;
+        if (a.slices > 1) {
+            if constexpr (can_slice(NT, VEC, BB, PP)) {       // (the dispatch offers no other variant to a sliced plan)
+                hipLaunchKernelGGL((chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP, true>), dim3(a.k * a.slices), dim3(NT), 0, s, a);
+            }
+            return;
+        }
+        auto kernel = chain_dense_reg_kernel<RowElem, kLoss, NT, EPT, VEC, BB, PP, false>;
         size_t claim = 0;
         if (a.helpers > 0) {
             // more than half of a compute unit's LDS per workgroup: chains and helpers each get a unit of their own
@@ -509,7 +534,7 @@ static void launch_variant(const ChainArgs &a, hipStream_t s)
         }
         ChainArgs b = a;
         if (claim == 0) b.helpers = 0;
-        hipLaunchKernelGGL(kernel, dim3(b.k * b.slices + b.helpers), dim3(NT), claim, s, b);
+        hipLaunchKernelGGL(kernel, dim3(b.k + b.helpers), dim3(NT), claim, s, b);
     }
 }
 
@@ -529,7 +554,8 @@ hipError_t WPSGD_CAT(dense_reg_dispatch_, WPSGD_SUFFIX)(Plan &p, const ChainArgs
 {
 #define WPSGD_TRY(NT, EPT, VEC, BB, PP)                                                        \
     if (p.threads == NT && p.ept == EPT && p.vec == VEC && (p.block_steps == 0 || p.block_steps == BB) && \
-        (p.rows == 0 || p.rows == rows_kind(PP)) && (p.prefetch == 0 || p.prefetch == (PP < 0 ? 1 : PP))) { \
+        (p.rows == 0 || p.rows == rows_kind(PP)) && (p.prefetch == 0 || p.prefetch == (PP < 0 ? 1 : PP)) && \
+        (p.slices <= 1 || can_slice(NT, VEC, BB, PP))) {                                        \
         p.block_steps = BB;                                                                    \
         p.prefetch = PP < 0 ? 1 : PP;                                                          \
         p.rows = rows_kind(PP);                                                                \
