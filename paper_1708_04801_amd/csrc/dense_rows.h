@@ -250,13 +250,30 @@ __device__ inline bool slices_all_reduce(const ChainArgs &a, int chain_block, in
     } else {
         // lanes 0..7 hold the slices' sums (zero beyond the last slice); three exchange levels among
         // those eight lanes add them in one fixed tree, the same in every slice and wave
+        if constexpr (NVAL == 3) {
+            // three sums level by level: each one's next level is two instructions behind its last
+            float t0 = lane < a.slices ? __uint_as_float(got[0]) : 0.0f;
+            float t1 = lane < a.slices ? __uint_as_float(got[1]) : 0.0f;
+            float t2 = lane < a.slices ? __uint_as_float(got[2]) : 0.0f;
+#define WPSGD_DPP3(CTRL)                                                       \
+    "v_add_f32_dpp %0, %0, %0 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+    "v_add_f32_dpp %1, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t" \
+    "v_add_f32_dpp %2, %2, %2 " CTRL " row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            asm volatile("s_nop 1\n\t" WPSGD_DPP3("quad_perm:[1,0,3,2]") WPSGD_DPP3("quad_perm:[2,3,0,1]") WPSGD_DPP3("row_half_mirror")
+                         : "+v"(t0), "+v"(t1), "+v"(t2));
+#undef WPSGD_DPP3
+            w[0] = (uint32_t)__builtin_amdgcn_readfirstlane(__float_as_int(t0));
+            w[1] = (uint32_t)__builtin_amdgcn_readfirstlane(__float_as_int(t1));
+            w[2] = (uint32_t)__builtin_amdgcn_readfirstlane(__float_as_int(t2));
+        } else {
 #pragma unroll
-        for (int r = 0; r < NVAL; ++r) {
-            float t = lane < a.slices ? __uint_as_float(got[r]) : 0.0f;
-            t += from_other_lane<0xB1>(t);      // quad_perm [1,0,3,2]
-            t += from_other_lane<0x4E>(t);      // quad_perm [2,3,0,1]
-            t += from_other_lane<0x141>(t);     // row_half_mirror
-            w[r] = (uint32_t)__builtin_amdgcn_readfirstlane(__float_as_int(t));
+            for (int r = 0; r < NVAL; ++r) {
+                float t = lane < a.slices ? __uint_as_float(got[r]) : 0.0f;
+                t += from_other_lane<0xB1>(t);      // quad_perm [1,0,3,2]
+                t += from_other_lane<0x4E>(t);      // quad_perm [2,3,0,1]
+                t += from_other_lane<0x141>(t);     // row_half_mirror
+                w[r] = (uint32_t)__builtin_amdgcn_readfirstlane(__float_as_int(t));
+            }
         }
     }
     return true;
