@@ -167,7 +167,8 @@ def main() -> int:
     # What k compute units can draw from HBM on their own: k workgroups streaming rows of this
     # size with no arithmetic, times the share of that time the chains are alive.  (One compute
     # unit draws 55-60 GB/s however much it keeps in flight; the chain kernel gets past this figure
-    # by letting helper workgroups on idle compute units pull the rows into L2 first.)
+    # by letting helper workgroups on idle compute units pull the rows into L2 first, or by cutting
+    # each chain into column slices that run on several compute units.)
     if not w.is_csr and w.row_bytes() >= 4096 and w.row_bytes() % 16 == 0:
         rows = int(min(w.n_steps.max(), 4096))
         best = None

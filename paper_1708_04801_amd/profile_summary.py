@@ -120,8 +120,8 @@ def main():
             f"What {ceil['workgroups']} compute units draw from HBM on their own (`stream_rows_kernel`, no arithmetic): "
             f"{ceil['streaming_GBps']:.1f} GB/s; chains are alive {100 * ceil['alive_fraction']:.1f} % of the kernel's "
             f"duration on average, which would allow {ceil['attainable_GBps']:.1f} GB/s; the chain kernel reaches "
-            f"{100 * ceil['frac_of_attainable']:.1f} % of that (more than all of it where helper workgroups on idle "
-            "compute units pull the rows into L2 ahead of the chains).",
+            f"{100 * ceil['frac_of_attainable']:.1f} % of that (more than all of it where idle compute units take part: helper "
+            "workgroups that pull the rows into L2 ahead of the chains, or chains cut into column slices).",
         ]
     if "us_per_step_longest_chain" in roof:
         lines += ["", f"Longest chain: {roof['longest_chain_steps']} steps, {roof['us_per_step_longest_chain']:.3f} us per step "
