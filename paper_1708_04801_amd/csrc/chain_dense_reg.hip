@@ -356,14 +356,27 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     c[b] = cy[b] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(zy[b] * dot));
                 }
             }
+            if constexpr (SLICED && P > 1 && B == 2) {
+                // A slice's next poll waits for these requests (loads return in order): they go out
+                // between the two halves of the update rather than behind it.  Per element the
+                // additions keep their order.
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) {
-#pragma unroll
-                for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
-            }
-            if constexpr (P > 1 && kFirstHalf < B) {
-                __builtin_amdgcn_sched_barrier(0);        // keep these requests behind the update
+                for (int e = 0; e < EPT; ++e) v[e] += c[0] * (TV)x[u][0].at(e);
+                __builtin_amdgcn_sched_barrier(0);
                 issue_rows(u_prev, next_rows, kFirstHalf, B);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) v[e] += c[1] * (TV)x[u][1].at(e);
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+#pragma unroll
+                    for (int b = 0; b < B; ++b) v[e] += c[b] * (TV)x[u][b].at(e);
+                }
+                if constexpr (P > 1 && kFirstHalf < B) {
+                    __builtin_amdgcn_sched_barrier(0);        // keep these requests behind the update
+                    issue_rows(u_prev, next_rows, kFirstHalf, B);
+                }
             }
             if constexpr (P == 1) {                       // a single slot: refill once it is free
                 __amdgpu_buffer_rsrc_t rx[B];
