@@ -60,6 +60,7 @@ def lib():
         L.oracle_weights_rate.argtypes = [i64, pi64, f64, pf64]
         L.oracle_weights.argtypes = [i64, pi64, f64, f64, pf64]
         L.oracle_benefit_margin.argtypes = [i64, pi64, f64, pf64]
+        L.oracle_span_condition.argtypes = [i64, pi64, f64, pf64]
         L.oracle_combine.argtypes = [pf64, pf64, i64, i64, pf64]
         L.oracle_objective.argtypes = [vp, i32, pi64, pi32, pf32, i64, i64, pf32, pf64, f64, i32, pf64, pf64]
         L.oracle_run_chains.argtypes = [vp, i32, pi64, pi32, pf32, i64, i64, pf32, i64, pi64, pi64,
@@ -169,6 +170,15 @@ def benefit_margin(n_steps, rate):
     return out.value
 
 
+def span_condition(steps_per_span, rate):
+    """Left side of the validity condition below Deduction 2 (valid when < 1)."""
+    n = np.ascontiguousarray(steps_per_span, dtype=np.int64)
+    out = ctypes.c_double(0.0)
+    _check(lib().oracle_span_condition(n.size, _p(n, ctypes.c_int64), float(rate),
+                                       ctypes.byref(out)), "span_condition")
+    return out.value
+
+
 def combine(W, a):
     W = np.ascontiguousarray(W, dtype=np.float64)
     a = np.ascontiguousarray(a, dtype=np.float64)
@@ -224,6 +234,27 @@ def run_chains(X, y, n_steps, eta, lam, loss, seed, chain_ids=None, csr_mode=PLA
                                  _p(mm, ctypes.c_double))
     _check(rc, "run_chains")
     return W, mm
+
+
+def run_spans(X, y, steps_per_span, n_spans, eta, lam, loss, seed, w0=None, shards=False,
+              csr_mode=PLAIN):
+    """Periodic weighted averaging (Section III, Deduction 2): n_spans times, chain i takes
+    steps_per_span[i] steps from the common vector v, continuing its own visit order, and v
+    becomes the Eq. 6 weighted sum of the chains' results.  The steps themselves are sgd(),
+    the weights weights(), the sum combine(): nothing else happens here.  Returns v."""
+    n = np.ascontiguousarray(steps_per_span, dtype=np.int64)
+    k = n.size
+    v = np.zeros(X.d, dtype=np.float64) if w0 is None else np.array(w0, dtype=np.float64).copy()
+    a = weights(n, eta, lam)
+    for s in range(int(n_spans)):
+        W = np.zeros((k, X.d), dtype=np.float64)
+        for i in range(k):
+            first = s * int(n[i])
+            idx = shard_indices(seed, i, k, first, int(n[i]), X.m) if shards else \
+                sample_indices(seed, i, first, int(n[i]), X.m)
+            W[i], _ = sgd(X, y, idx, eta, lam, loss, w0=v, csr_mode=csr_mode)
+        v = combine(W, a)
+    return v
 
 
 def wpsgd(X, y, n_steps, eta, lam, loss, seed, threads=None):

@@ -313,6 +313,24 @@ int oracle_benefit_margin(int64_t k, const int64_t *n_steps, double rate, double
     return ORACLE_OK;
 }
 
+/* Periodic averaging (Section III, Deduction 2): with chain j taking D_j steps between two
+ * averages and the fastest taking span = max_j D_j, so that T_j = span - D_j, the text below the
+ * deduction asks for  k / (sum_j rate^{T_j}) * rate^{span} < 1.  *value receives the left side. */
+int oracle_span_condition(int64_t k, const int64_t *steps_per_span, double rate, double *value)
+{
+    if (k < 1 || !steps_per_span || !value || !(rate > 0.0) || rate > 1.0) return ORACLE_BAD_ARG;
+    int64_t span = 0;
+    for (int64_t j = 0; j < k; ++j) {
+        if (steps_per_span[j] < 0) return ORACLE_BAD_ARG;
+        if (steps_per_span[j] > span) span = steps_per_span[j];
+    }
+    double total = 0.0;
+    for (int64_t j = 0; j < k; ++j)
+        total += pow(rate, (double)(span - steps_per_span[j]));
+    *value = (double)k / total * pow(rate, (double)span);
+    return ORACLE_OK;
+}
+
 /* v = sum_i a_i * W[i,:]  (last line of Algorithm 1), i ascending. */
 int oracle_combine(const double *W, const double *a, int64_t k, int64_t d, double *v)
 {

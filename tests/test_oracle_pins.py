@@ -469,6 +469,67 @@ def test_weighted_output_is_the_weighted_sum_of_chain_outputs():
     np.testing.assert_allclose(v, (raw / raw.sum()) @ W, rtol=1e-13, atol=1e-16)
 
 
+# ---------------------------------------------------------------- periodic averaging (Section III, Deduction 2)
+
+def test_one_chain_averaged_with_itself_is_one_long_chain():
+    """k = 1: the average of one model is that model, so S spans of n steps are S*n sequential
+    steps of the chain's own stream (pins the restart vector and the stream offsets)."""
+    X, y = _small_problem()
+    for loss in (orc.HINGE, orc.LOGISTIC):
+        v = orc.run_spans(X, y, [70], 4, 0.05, 0.01, loss, seed=3)
+        w, _ = orc.sgd(X, y, orc.sample_indices(3, 0, 0, 280, X.m), 0.05, 0.01, loss)
+        assert np.array_equal(v, w)
+    start = np.linspace(-1.0, 1.0, X.d)
+    v = orc.run_spans(X, y, [70], 2, 0.05, 0.01, orc.HINGE, seed=3, w0=start)
+    w, _ = orc.sgd(X, y, orc.sample_indices(3, 0, 0, 140, X.m), 0.05, 0.01, orc.HINGE, w0=start)
+    assert np.array_equal(v, w)
+    v = orc.run_spans(X, y, [40], 3, 0.05, 0.01, orc.HINGE, seed=3, shards=True)
+    w, _ = orc.sgd(X, y, orc.shard_indices(3, 0, 1, 0, 120, X.m), 0.05, 0.01, orc.HINGE)
+    assert np.array_equal(v, w)
+
+
+def test_one_span_is_algorithm_1_and_equal_chains_take_the_plain_mean_every_span():
+    X, y = _small_problem()
+    n = [90, 30, 60]
+    v1, _, _ = orc.wpsgd(X, y, n, 0.5, 0.1, orc.HINGE, seed=2)
+    assert np.array_equal(orc.run_spans(X, y, n, 1, 0.5, 0.1, orc.HINGE, seed=2), v1)
+    # second span by hand: every chain restarts from v1 at its own offset, weights as in Eq. 6
+    rho = 0.95
+    raw = np.array([1.0, rho ** 60, rho ** 30])
+    W2 = np.stack([orc.sgd(X, y, orc.sample_indices(2, i, n[i], n[i], X.m), 0.5, 0.1, orc.HINGE, w0=v1)[0]
+                   for i in range(3)])
+    np.testing.assert_allclose(orc.run_spans(X, y, n, 2, 0.5, 0.1, orc.HINGE, seed=2),
+                               (raw / raw.sum()) @ W2, rtol=1e-12, atol=1e-15)
+    # equal chains: the plain mean after each span (the averaging of Deduction 1)
+    v = np.zeros(X.d)
+    for s in range(3):
+        v = np.mean([orc.sgd(X, y, orc.sample_indices(7, i, 50 * s, 50, X.m), 0.05, 0.01, orc.LOGISTIC, w0=v)[0]
+                     for i in range(4)], axis=0)
+    np.testing.assert_allclose(orc.run_spans(X, y, [50] * 4, 3, 0.05, 0.01, orc.LOGISTIC, seed=7), v,
+                               rtol=1e-12, atol=1e-15)
+
+
+def test_span_validity_condition():
+    """k / sum_j rho^{T_j} * rho^{span} (below Deduction 2): rho^span for equal chains, k times
+    the fastest chain's Eq. 6 weight times rho^span in general, 1 without regularisation."""
+    assert orc.span_condition([50, 50, 50], 0.99) == pytest.approx(0.99 ** 50, rel=1e-14)
+    assert orc.span_condition([100, 0], 0.999) == pytest.approx(2.0 / (1.0 + 0.999 ** 100) * 0.999 ** 100, rel=1e-14)
+    n = [100, 80, 60, 100]
+    a = orc.weights_rate(n, 0.999)
+    assert orc.span_condition(n, 0.999) == pytest.approx(4 * a[0] * 0.999 ** 100, rel=1e-13)
+    assert orc.span_condition([7, 3, 5], 1.0) == 1.0
+    # With T_j = span - D_j the expression equals k / sum_j rho^{-D_j}: the harmonic-mean form shows
+    # that it never exceeds 1 and reaches 1 only when no chain moves.
+    for n, rate in (([10, 3, 0, 7], 0.97), ([1, 1], 0.5), ([0, 0, 5], 0.999)):
+        assert orc.span_condition(n, rate) == pytest.approx(len(n) / sum(rate ** -d for d in n), rel=1e-13)
+        assert orc.span_condition(n, rate) < 1.0
+    assert orc.span_condition([0, 0, 0], 0.9) == 1.0
+    with pytest.raises(Exception):
+        orc.span_condition([3, -1], 0.9)
+    with pytest.raises(Exception):
+        orc.span_condition([3, 1], 1.5)
+
+
 # ---------------------------------------------------------------- objective (Eq. 3, Eq. 4)
 
 def test_objective_closed_forms():
