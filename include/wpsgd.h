@@ -153,6 +153,31 @@ size_t wpsgd_combine_workspace(int k, int64_t d);
 int wpsgd_combine(const float *W, const double *a, int k, int64_t d, float *w_out,
                   void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- periodic weighted averaging (Section III, Deduction 2) ----
+ * n_spans times over: every chain i takes steps_per_span[i] steps from the common vector v (w_start,
+ * or zero, the first time), continuing its own sample stream where the previous span left it, and v
+ * becomes sum_i a_i w_i with the weights of Eq. 6 for steps_per_span.  The largest entry of
+ * steps_per_span is the paper's `span`, counted on the fastest node.  One span is Algorithm 1.
+ * Everything is queued on `stream`; the call may wait for earlier spans' small host-to-device
+ * copies (step counts, weights), never for a kernel it has queued itself.
+ *   steps_per_span  HOST, k entries >= 0, at least one > 0; steps_per_span[i] * n_spans <= 2^62
+ *   w_start         DEVICE, d entries fp32, or NULL for zero
+ *   w_out           DEVICE out, d entries fp32: v after the last span (may be w_start)
+ *   workspace       DEVICE scratch of at least wpsgd_run_spans_workspace(...) bytes, 256-byte aligned
+ *                   (the chains' models, and what wpsgd_run_chains and wpsgd_combine need)
+ * Errors: as wpsgd_run_chains_from and wpsgd_combine; INVALID_ARG for n_spans < 1.             */
+size_t wpsgd_run_spans_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *plan);
+int wpsgd_run_spans(const wpsgd_matrix *X, const float *y, int k, const int64_t *steps_per_span, int64_t n_spans,
+                    double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
+                    const float *w_start, float *w_out, void *workspace, size_t workspace_bytes,
+                    const wpsgd_plan *plan, void *stream);
+
+/* The expression the text below Deduction 2 asks to keep under 1 for averaging every span to be
+ * valid:  *value = k / (sum_j rate^{T_j}) * rate^{span},  span = max_j steps_per_span[j],
+ * T_j = span - steps_per_span[j].  (It equals k / sum_j rate^{-steps_per_span[j]}, so as printed it
+ * is below 1 whenever rate < 1 and some chain moves.)  HOST only, fp64.                         */
+int wpsgd_span_condition(int k, const int64_t *steps_per_span, double rate, double *value);
+
 /* ---- objective and prediction error of a model (Eq. 3 with the loss of Eq. 4) ----
  *   out[0] = lambda/2 * |w|^2 + (1/m) * sum_j L(x_j, y_j, w.x_j)
  *   out[1] = fraction of rows with y_j * (w.x_j) <= 0     (the error rate the experiments report)

@@ -28,6 +28,7 @@ EXPORTS = [
     "wpsgd_sample_indices_device", "wpsgd_strerror", "wpsgd_last_hip_error", "wpsgd_describe_plan",
     "wpsgd_stream_rows", "wpsgd_objective_workspace", "wpsgd_objective",
     "wpsgd_run_chains_from", "wpsgd_shard_indices", "wpsgd_shard_indices_device",
+    "wpsgd_run_spans_workspace", "wpsgd_run_spans", "wpsgd_span_condition",
 ]
 
 
@@ -70,6 +71,10 @@ def load():
     L.wpsgd_run_chains_workspace.restype = sz
     L.wpsgd_run_chains.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, sz, pp, vp]
     L.wpsgd_run_chains_from.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, ci, vp, vp, vp, vp, sz, pp, vp]
+    L.wpsgd_run_spans_workspace.argtypes = [pm, ci, ci, pp]
+    L.wpsgd_run_spans_workspace.restype = sz
+    L.wpsgd_run_spans.argtypes = [pm, vp, ci, vp, i64, f64, f64, ci, u64, ci, vp, vp, vp, sz, pp, vp]
+    L.wpsgd_span_condition.argtypes = [ci, vp, f64, vp]
     L.wpsgd_shard_indices.argtypes = [u64, ci, ci, i64, i64, i64, vp]
     L.wpsgd_shard_indices_device.argtypes = [u64, ci, ci, i64, i64, i64, vp, vp]
     L.wpsgd_weights.argtypes = [ci, vp, f64, f64, vp]
@@ -232,6 +237,43 @@ def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, s
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_run_chains_from")
     return W
+
+
+def wpsgd_run_spans(X: Matrix, y: torch.Tensor, steps_per_span, n_spans, eta, lam, loss, seed,
+                    w_start: Optional[torch.Tensor] = None, sampling=0, w_out: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None, plan=None, stream=None) -> torch.Tensor:
+    """Periodic weighted averaging: n_spans times, chains of steps_per_span steps from the common
+    vector, then the Eq. 6 weighted sum.  Returns the vector after the last span (d float32)."""
+    n = _steps(steps_per_span)
+    k = int(n.size)
+    dev = y.device
+    assert y.is_cuda and y.dtype == torch.float32 and y.numel() == X.m
+    if w_start is not None:
+        assert w_start.is_cuda and w_start.dtype == torch.float32 and w_start.is_contiguous() and w_start.numel() == X.d
+    if w_out is None:
+        w_out = torch.empty(X.d, dtype=torch.float32, device=dev)
+    assert w_out.is_cuda and w_out.dtype == torch.float32 and w_out.is_contiguous() and w_out.numel() == X.d
+    cm = X.c_struct()
+    pl = _plan(plan)
+    if workspace is None:
+        need = load().wpsgd_run_spans_workspace(ctypes.byref(cm), k, int(loss), pl)
+        workspace = _workspace(need, dev)
+    rc = load().wpsgd_run_spans(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, int(n_spans), float(eta),
+                                float(lam), int(loss), int(seed), int(sampling),
+                                w_start.data_ptr() if w_start is not None else None, w_out.data_ptr(),
+                                workspace.data_ptr(), workspace.numel(), pl, _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_run_spans")
+    return w_out
+
+
+def wpsgd_span_condition(steps_per_span, rate) -> float:
+    n = _steps(steps_per_span)
+    out = ctypes.c_double(0.0)
+    rc = load().wpsgd_span_condition(int(n.size), n.ctypes.data, float(rate), ctypes.addressof(out))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_span_condition")
+    return out.value
 
 
 def wpsgd_weights(n_steps, eta, lam) -> np.ndarray:

@@ -553,6 +553,63 @@ int wpsgd_combine(const float *W, const double *a, int k, int64_t d, float *w_ou
     return e == hipSuccess ? WPSGD_OK : hip_fail(e);
 }
 
+size_t wpsgd_run_spans_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wpsgd_plan *plan)
+{
+    const size_t chains = wpsgd_run_chains_workspace(X, k, loss, plan);
+    if (chains == 0) return 0;
+    return align256((size_t)k * (size_t)X->d * sizeof(float)) + chains + wpsgd_combine_workspace(k, X->d);
+}
+
+int wpsgd_run_spans(const wpsgd_matrix *X, const float *y, int k, const int64_t *steps_per_span, int64_t n_spans,
+                    double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
+                    const float *w_start, float *w_out, void *workspace, size_t workspace_bytes,
+                    const wpsgd_plan *plan, void *stream)
+{
+    int rc = check_matrix(X);
+    if (rc != WPSGD_OK) return rc;
+    rc = check_steps(k, steps_per_span);
+    if (rc != WPSGD_OK) return rc;
+    if (!w_out || n_spans < 1) return WPSGD_INVALID_ARG;
+    int64_t span = 0;
+    for (int i = 0; i < k; ++i) span = std::max(span, steps_per_span[i]);
+    if (span < 1 || span > ((int64_t)1 << 62) / n_spans) return WPSGD_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
+    const size_t models = align256((size_t)k * (size_t)X->d * sizeof(float));
+    const size_t chains = wpsgd_run_chains_workspace(X, k, loss, plan);
+    const size_t average = wpsgd_combine_workspace(k, X->d);
+    if (chains == 0) return WPSGD_UNSUPPORTED;
+    if (workspace_bytes < models + chains + average) return WPSGD_WORKSPACE_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace);
+    float *W = reinterpret_cast<float *>(ws);
+    std::vector<double> a(k);
+    rc = wpsgd_weights(k, steps_per_span, eta, lambda, a.data());
+    if (rc != WPSGD_OK) return rc;
+    std::vector<int64_t> first(k);
+    for (int64_t sp = 0; sp < n_spans; ++sp) {
+        for (int i = 0; i < k; ++i) first[i] = sp * steps_per_span[i];
+        rc = wpsgd_run_chains_from(X, y, k, steps_per_span, eta, lambda, loss, seed, sampling, sp == 0 ? w_start : w_out,
+                                   first.data(), W, ws + models, chains, plan, stream);
+        if (rc != WPSGD_OK) return rc;
+        rc = wpsgd_combine(W, a.data(), k, X->d, w_out, ws + models + chains, average, stream);
+        if (rc != WPSGD_OK) return rc;
+    }
+    return WPSGD_OK;
+}
+
+int wpsgd_span_condition(int k, const int64_t *steps_per_span, double rate, double *value)
+{
+    int rc = check_steps(k, steps_per_span);
+    if (rc != WPSGD_OK) return rc;
+    if (!value || !(rate > 0.0) || !(rate <= 1.0)) return WPSGD_INVALID_ARG;
+    int64_t span = 0;
+    for (int i = 0; i < k; ++i) span = std::max(span, steps_per_span[i]);
+    const double log_rate = std::log(rate);
+    double total = 0.0;
+    for (int i = 0; i < k; ++i) total += std::exp((double)(span - steps_per_span[i]) * log_rate);
+    *value = (double)k / total * std::exp((double)span * log_rate);
+    return WPSGD_OK;
+}
+
 size_t wpsgd_objective_workspace(const wpsgd_matrix *X)
 {
     if (check_matrix(X) != WPSGD_OK) return 0;

@@ -532,6 +532,53 @@ def test_periodic_averaging_restarts_chains_from_the_weighted_average():
     assert np.linalg.norm(v2 - vo2) / np.linalg.norm(vo2) <= TOL
 
 
+def _check_spans(w, steps, n_spans, label, sampling=0, start=None, plan=None):
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    Xo = orc.CSR(w.row_ptr, w.col_idx, w.vals, w.d) if w.is_csr else orc.Dense(w.dense)
+    w0 = None if start is None else torch.from_numpy(start).cuda()
+    v = api.wpsgd_run_spans(X, y, steps, n_spans, w.eta, w.lam, w.loss, w.seed, w_start=w0, sampling=sampling, plan=plan)
+    torch.cuda.synchronize()
+    vo = orc.run_spans(Xo, w.y, steps, n_spans, w.eta, w.lam, w.loss, w.seed,
+                       w0=None if start is None else start.astype(np.float64), shards=sampling == api.SAMPLE_SHARDS)
+    err = rel_l2(v.cpu().numpy(), vo)
+    assert err <= TOL, f"{label}: after {n_spans} spans rel L2 {err:.3e}"
+    return v
+
+
+def test_span_averaging_entry_point_matches_the_oracle():
+    """wpsgd_run_spans (Section III, Deduction 2) against the oracle's loop over its own single-chain
+    routine: dense and sparse rows, both losses and sampling schemes, a start vector, idle chains."""
+    w = wl.tiny_hinge()
+    _check_spans(w, [50, 40, 30, 20], 5, "tiny hinge")
+    _check_spans(w, [50, 40, 30, 20], 3, "tiny hinge on shards", sampling=api.SAMPLE_SHARDS)
+    rng = np.random.default_rng(12)
+    m, d = 400, 4096
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(X @ rng.standard_normal(d) >= 0, 1.0, -1.0).astype(np.float32)
+    wd = wl.Workload("spans_dense", wl.LOGISTIC, 0.5, 1e-2, 9, np.array([64, 0, 33, 64, 7], dtype=np.int64), y, m, d, dense=X)
+    start = (0.1 * rng.standard_normal(d)).astype(np.float32)
+    v = _check_spans(wd, wd.n_steps, 4, "dense logistic from a start vector", start=start)
+    # one span is the whole of Algorithm 1; the output may overwrite the start vector
+    Xg, yg = api.matrix_from_workload(wd), torch.from_numpy(wd.y).cuda()
+    one = api.wpsgd_run_spans(Xg, yg, wd.n_steps, 1, wd.eta, wd.lam, wd.loss, wd.seed)
+    W = api.wpsgd_run_chains(Xg, yg, wd.n_steps, wd.eta, wd.lam, wd.loss, wd.seed)
+    assert torch.equal(one, api.wpsgd_combine(W, api.wpsgd_weights(wd.n_steps, wd.eta, wd.lam)))
+    buf = torch.from_numpy(start).cuda()
+    api.wpsgd_run_spans(Xg, yg, wd.n_steps, 4, wd.eta, wd.lam, wd.loss, wd.seed, w_start=buf, w_out=buf)
+    assert torch.equal(buf, v)
+    ws = wl.sparse_hinge(m=3000, d=1 << 14, k=5, n_median=150)
+    for loss in (wl.HINGE, wl.LOGISTIC):
+        ws.loss = loss
+        _check_spans(ws, np.minimum(ws.n_steps, 120), 3, f"sparse loss {loss}")
+    with pytest.raises(api.WpsgdError) as e:
+        api.wpsgd_run_spans(Xg, yg, wd.n_steps, 0, wd.eta, wd.lam, wd.loss, wd.seed)
+    assert e.value.status == api.INVALID_ARG
+    with pytest.raises(api.WpsgdError) as e:
+        api.wpsgd_run_spans(Xg, yg, [0, 0, 0], 2, wd.eta, wd.lam, wd.loss, wd.seed)
+    assert e.value.status == api.INVALID_ARG
+
+
 def test_run_chains_from_rejects_negative_offsets():
     w = wl.tiny_hinge()
     X = api.matrix_from_workload(w)

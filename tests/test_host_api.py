@@ -51,6 +51,18 @@ def test_benefit_margin_matches_oracle():
     assert api.wpsgd_benefit_margin([3, 1], 0.75) == pytest.approx(orc.benefit_margin([3, 1], 0.75), rel=1e-14)
 
 
+def test_span_condition_matches_oracle_and_closed_forms():
+    assert api.wpsgd_span_condition([50, 50, 50], 0.99) == pytest.approx(0.99 ** 50, rel=1e-13)
+    assert api.wpsgd_span_condition([10, 3, 0, 7], 0.97) == pytest.approx(4 / sum(0.97 ** -d for d in (10, 3, 0, 7)), rel=1e-13)
+    for n, r in (([1000, 800, 600, 400], 1 - 1e-5), ([3, 1], 0.75), ([0, 0, 9], 1.0)):
+        assert api.wpsgd_span_condition(n, r) == pytest.approx(orc.span_condition(n, r), rel=1e-13)
+    for bad in (lambda: api.wpsgd_span_condition([3, -1], 0.9), lambda: api.wpsgd_span_condition([3, 1], 0.0),
+                lambda: api.wpsgd_span_condition([3, 1], 1.5)):
+        with pytest.raises(api.WpsgdError) as err:
+            bad()
+        assert err.value.status == api.INVALID_ARG
+
+
 @pytest.mark.parametrize("row", golden_rows("sample_index_streams.txt"))
 def test_host_sample_stream_golden(row):
     head, tail = row.split(":")
@@ -157,3 +169,7 @@ def test_workspace_sizes():
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.LOGISTIC)
     assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 2048 + 1024
     assert api.wpsgd_combine_workspace(64, 4096) == 512
+    # spans: the chains' models, then what the chains and the average need
+    fm = _FakeMatrix(4096, 64)
+    assert api.load().wpsgd_run_spans_workspace(ctypes.byref(fm.c_struct()), 4, api.HINGE, None) == \
+        1024 + api.wpsgd_run_chains_workspace(fm, 4, api.HINGE) + 256
