@@ -92,7 +92,12 @@ typedef struct wpsgd_plan {
                             (logistic: up to 4 steps per round; hinge: up to 2).  k*slices must not exceed
                             the compute units.  0: choose (chains whose rows need more than 256
                             threads, compute units permitting); 1: a chain is one workgroup; 2..8: that
-                            many, which must be what some 256-thread shape needs to cover d             */
+                            many, which must be what some 256-thread shape needs to cover d.
+                            The slices of a chain wait for each other, so all k*slices workgroups must
+                            be running at once: on a device that is busy with other kernels some may not
+                            be seated in time, and a slice that has waited in vain (some tens of
+                            milliseconds) ends and fills its columns of W with NaN.  Callers who share
+                            the device pass slices = 1.                                               */
 } wpsgd_plan;
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----
