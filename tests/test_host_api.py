@@ -160,6 +160,30 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
         assert err.value.status == api.INVALID_ARG
 
 
+def test_planner_shapes_cover_the_row_for_any_size():
+    """Whatever d, k, storage and loss: a register plan's lanes cover every column, a sliced plan
+    leaves no slice empty and never asks for more workgroups than the device has compute units,
+    and everything else falls to the kernel that keeps the model in HBM."""
+    import re
+    d_values = [1, 63, 64, 65, 255, 1000, 4096, 4100, 8192, 12000, 16384, 20000, 32768, 40000, 65536, 70000, 131072, 200000]
+    for dtype in (api.F32, api.BF16):
+        for loss in (api.HINGE, api.LOGISTIC):
+            for k in (1, 9, 32, 33, 64, 129, 3000):
+                for d in d_values:
+                    if dtype == api.BF16 and d % 8:
+                        continue
+                    text = api.wpsgd_describe_plan(_FakeMatrix(1 << 16, d, dtype), k, loss)
+                    if text.startswith("dense_mem"):
+                        continue
+                    f = {m.group(1): int(m.group(2)) for m in re.finditer(r"(nt|ept|vec|B|P|slices|helpers)=(\d+)", text)}
+                    slices = f.get("slices", 1)
+                    assert f["nt"] * f["ept"] * slices >= d, (text, d, k)
+                    assert slices == 1 or f["nt"] * f["ept"] * (slices - 1) < d, (text, d, k)
+                    assert k * slices + k * f.get("helpers", 0) <= 256 or (slices == 1 and "helpers" not in f), (text, d, k)
+                    assert 64 % (f["B"] * max(f["P"], 1)) == 0, (text, d, k)
+                    assert not ("slices" in f and "helpers" in f), (text, d, k)
+
+
 def test_workspace_sizes():
     # chain order + step counts + stream offsets + share descriptions + progress counters (256-byte slots)
     # + power table (1 KiB) + shuffled row order (4 bytes a row) + room for the model vectors in HBM
