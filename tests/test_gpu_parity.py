@@ -588,6 +588,87 @@ def test_run_chains_from_rejects_negative_offsets():
     assert e.value.status == api.INVALID_ARG
 
 
+# ------------------------------------------------------------------ random shapes and plans
+
+def _random_case(rng):
+    kind = rng.choice(["dense", "dense", "dense", "bf16", "csr"])
+    loss = int(rng.integers(0, 2))
+    k = int(rng.choice([1, 2, 3, 5, 8, 9, 16, 33]))
+    d = int([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 20000), rng.integers(20000, 70000),
+             rng.choice([64, 256, 4096, 8192, 16384, 32768, 65536]), rng.integers(1, 70000)][rng.integers(0, 6)])
+    if kind == "bf16" or rng.random() < 0.6:
+        d = max(8, d // 8 * 8)
+    m = int(rng.integers(max(k, 2), 400))
+    n = rng.integers(0, 160, size=k).astype(np.int64)
+    if rng.random() < 0.5:
+        n[rng.integers(0, k)] = int(rng.integers(160, 400))
+    eta, lam = float(rng.choice([0.5, 0.1, 0.02])), float(rng.choice([1e-2, 1e-3, 1e-5, 0.0]))
+    seed = int(rng.integers(0, 2 ** 40))
+    shards, use_start = bool(rng.random() < 0.25), bool(rng.random() < 0.3)
+    plan, r = None, rng.random()
+    if kind != "csr":
+        if r < 0.15:
+            plan = {"slices": int(rng.choice([2, 3, 4, 8]))}
+        elif r < 0.25:
+            plan = {"block_steps": int(rng.choice([1, 2, 4]))}
+        elif r < 0.30:
+            plan = {"helpers": int(rng.choice([1, 2, 3]))}
+        elif r < 0.35:
+            plan = {"rows": 4}
+        elif r < 0.40:
+            plan = {"state_in_hbm": 1}
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    if kind == "csr":
+        d = max(d, 64)
+        rp, ci, va = [0], [], []
+        for _ in range(m):
+            ln = int(min(d, max(1, rng.poisson(20))))
+            ci.append(np.sort(rng.choice(d, size=ln, replace=False)).astype(np.int32))
+            vals = rng.standard_normal(ln).astype(np.float32)
+            va.append(vals / max(np.linalg.norm(vals), 1e-6))
+            rp.append(rp[-1] + ln)
+        w = wl.Workload("random", loss, eta, lam, seed, n, y, m, d, row_ptr=np.array(rp, dtype=np.int64),
+                        col_idx=np.concatenate(ci), vals=np.concatenate(va))
+    else:
+        X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+        w = wl.Workload("random", loss, eta, lam, seed, n, y, m, d, dense=wl.f32_to_bf16_bits(X) if kind == "bf16" else X)
+    start = (0.3 * rng.standard_normal(d)).astype(np.float32) if use_start else None
+    return w, plan, shards, start
+
+
+@pytest.mark.parametrize("batch", range(4))
+def test_random_shapes_plans_sampling_and_start_vectors(batch):
+    """Seeded random cases (widths 1..70000, 1..33 chains, all storages, forced and default plans,
+    both sampling schemes, with and without a start vector): every chain against the oracle."""
+    ran = 0
+    for it in range(40):
+        rng = np.random.default_rng(7_000_003 * (batch + 1) + it)
+        w, plan, shards, start = _random_case(rng)
+        X = api.matrix_from_workload(w)
+        try:
+            desc = api.wpsgd_describe_plan(X, w.k, w.loss, plan)
+        except api.WpsgdError as e:
+            assert e.status == api.UNSUPPORTED            # a forced plan this shape has no kernel for
+            continue
+        W = api.wpsgd_run_chains_from(X, torch.from_numpy(w.y).cuda(), w.n_steps, w.eta, w.lam, w.loss, w.seed,
+                                      w_start=None if start is None else torch.from_numpy(start).cuda(),
+                                      sampling=api.SAMPLE_SHARDS if shards else 0, plan=plan)
+        torch.cuda.synchronize()
+        Wg = W.cpu().numpy().astype(np.float64)
+        Xo = oracle_matrix(w)
+        for i in range(w.k):
+            idx = orc.shard_indices(w.seed, i, w.k, 0, int(w.n_steps[i]), w.m) if shards else \
+                orc.sample_indices(w.seed, i, 0, int(w.n_steps[i]), w.m)
+            wo, margin = orc.sgd(Xo, w.y, idx, w.eta, w.lam, w.loss, w0=None if start is None else start.astype(np.float64))
+            label = f"case {batch}/{it} chain {i} d={w.d} k={w.k} plan={plan} shards={shards} [{desc}]"
+            assert np.isfinite(Wg[i]).all(), label
+            if w.loss == wl.HINGE and margin < KINK:
+                continue
+            assert rel_l2(Wg[i], wo) <= TOL, label
+        ran += 1
+    assert ran >= 25
+
+
 # ------------------------------------------------------------------ partition-and-shuffle sampling
 
 def test_device_shard_stream_is_bit_exact():
