@@ -588,6 +588,40 @@ def test_run_chains_from_rejects_negative_offsets():
     assert e.value.status == api.INVALID_ARG
 
 
+# ------------------------------------------------------------------ streams
+
+def test_calls_on_side_streams_match_the_default_stream():
+    """The library queues on the caller's stream and keeps no device state of its own: the whole path on
+    two side streams at once (separate outputs and workspaces) gives the bits of the default stream."""
+    rng = np.random.default_rng(44)
+    m, d = 300, 1000
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    cases = [wl.Workload("side_a", wl.LOGISTIC, 0.5, 1e-2, 3, np.array([200, 90, 0, 150], dtype=np.int64), y, m, d, dense=X),
+             wl.Workload("side_b", wl.HINGE, 0.1, 1e-3, 4, np.array([64, 300, 17], dtype=np.int64), y, m, d, dense=X)]
+    Xg, yg = api.matrix_from_workload(cases[0]), torch.from_numpy(y).cuda()
+
+    def whole_path(w, stream=None):
+        W = api.wpsgd_run_chains(Xg, yg, w.n_steps, w.eta, w.lam, w.loss, w.seed, stream=stream)
+        v = api.wpsgd_combine(W, api.wpsgd_weights(w.n_steps, w.eta, w.lam), stream=stream)
+        spans = api.wpsgd_run_spans(Xg, yg, np.minimum(w.n_steps, 40), 3, w.eta, w.lam, w.loss, w.seed, stream=stream)
+        return W, v, spans
+
+    want = [whole_path(w) for w in cases]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = []
+    for w, st in zip(cases, streams):
+        with torch.cuda.stream(st):                       # torch allocates the outputs on that stream too
+            got.append(whole_path(w, stream=st))
+    for st in streams:
+        st.synchronize()
+    for g, wnt in zip(got, want):
+        for a_, b_ in zip(g, wnt):
+            assert torch.equal(a_, b_)
+    check_against_oracle(cases[0], got[0][0], label="side stream")
+
+
 # ------------------------------------------------------------------ random shapes and plans
 
 def _random_case(rng):
