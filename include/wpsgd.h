@@ -14,6 +14,8 @@
  *   - GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and is NOT synchronised: device outputs are complete
  *     when the stream reaches that point.  HOST outputs are complete on return.
+ *     HOST inputs travel through pinned staging buffers that belong to the call,
+ *     so a call that takes HOST arrays cannot be recorded into a HIP graph.
  *   - Step counts: n_steps[i] is the number of SGD steps chain i runs.  In the
  *     paper's notation the fastest node consumes t = max_i n_steps[i] samples
  *     and node i is T_i = t - n_steps[i] steps behind it (Algorithm 1; Table I).
