@@ -14,13 +14,14 @@ namespace wpsgd {
 constexpr int kCombineThreads = 256;
 
 template <int VEC, int RS>
-__global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float *__restrict__ W,
+__global__ __launch_bounds__(kCombineThreads) __attribute__((amdgpu_waves_per_eu(6))) void combine_kernel(const float *__restrict__ W,
                                                                   const double *__restrict__ a,
                                                                   int k, int64_t d,
                                                                   float *__restrict__ out)
 {
     constexpr int CT = kCombineThreads / RS;          // column-owning threads per workgroup
-    constexpr int UNROLL = 8;
+    constexpr int UNROLL = 16;                        // rows requested before the first is used
+    constexpr int TAIL = 4;                           // the same for the rows left over
     __shared__ double part[RS][CT][VEC];
     const int cx = threadIdx.x % CT;
     const int slice = threadIdx.x / CT;
@@ -42,11 +43,15 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float *_
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const float *p = W + (int64_t)(i + u) * d + col;
+                // every element of W is read once: non-temporal loads keep it from displacing anything
+                // (16 rows in flight and this hint: 4.3 -> 5.5 TB/s at k = 128, d = 2^20; the kernel
+                // must stay under 80 registers for that: at 94 it fell back to 4.5)
                 if constexpr (VEC == 4) {
-                    const float4 q = *reinterpret_cast<const float4 *>(p);
-                    x[u][0] = q.x; x[u][1] = q.y; x[u][2] = q.z; x[u][3] = q.w;
+                    typedef float f32x4 __attribute__((ext_vector_type(4)));
+                    const f32x4 q = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+                    x[u][0] = q[0]; x[u][1] = q[1]; x[u][2] = q[2]; x[u][3] = q[3];
                 } else {
-                    x[u][0] = p[0];
+                    x[u][0] = __builtin_nontemporal_load(p);
                 }
             }
 #pragma unroll
@@ -56,11 +61,25 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const float *_
                 for (int j = 0; j < VEC; ++j) acc[j] += w * (double)x[u][j];
             }
         }
-        for (; i < i1; ++i) {
-            const float *p = W + (int64_t)i * d + col;
-            const double w = a[i];
+        for (; i < i1; i += TAIL) {
+            const int left = i1 - i;
+            float x[TAIL][VEC];
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) acc[j] += w * (double)p[j];
+            for (int u = 0; u < TAIL; ++u) {
+                if (u < left) {
+                    const float *p = W + (int64_t)(i + u) * d + col;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) x[u][j] = p[j];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < TAIL; ++u) {
+                if (u < left) {
+                    const double w = a[i + u];
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) acc[j] += w * (double)x[u][j];
+                }
+            }
         }
     }
 
