@@ -69,8 +69,8 @@ def main() -> int:
     ap.add_argument("--helpers", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 "
-              "(chains shard across GPUs with one all-reduce, which is not part of this build)",
+        print("bench.py: this library runs on one GPU; --gpus must be 1 "
+              "(chains shard across GPUs with one all-reduce, which is not part of it)",
               file=sys.stderr)
         return 2
 

@@ -16,7 +16,7 @@
  *   - benefit condition  2 sum_i rate^{T_i} > sqrt(k) + k      (Eq. 7 / Eq. 9, Cor. 3/4)
  *
  * The paper does not define how a chain picks its n-th example beyond
- * "partition, shuffle, take the n-th"; this build replaces that by a
+ * "partition, shuffle, take the n-th"; this implementation replaces that by a
  * counter-based stream: Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11)
  * keyed by the seed, counter = (step, chain), first output word mapped to
  * [0, m) by multiply-shift.  Both sides implement it from the published

@@ -1,6 +1,6 @@
 """Turns the rocprofv3 output of the benchmark into the short summaries kept under profiles/.
 
-Inputs (directories written on the GPU machine, see the commands in the summary's header):
+Inputs (directories written by rocprofv3, see the commands in the summary's header):
     <prof>/stats/bench_kernel_stats.csv              rocprofv3 --kernel-trace --stats of bench.py
     <prof>/pmc_FETCH_SIZE, <prof>/pmc_WRITE_SIZE     rocprofv3 --pmc of bench.py
     <prof>/copy_FETCH_SIZE, <prof>/copy_WRITE_SIZE   the same counters on copy_probe.py (1 GiB copies)
@@ -11,7 +11,7 @@ Outputs:
                                       tagged with the digest of the kernel sources (bench.py
                                       quotes the number only while the sources are unchanged)
 
-    python -m paper_1708_04801_amd.profile_summary gpurun_out/prof dense_logistic
+    python -m paper_1708_04801_amd.profile_summary out/prof dense_logistic
 """
 from __future__ import annotations
 

@@ -550,7 +550,7 @@ def test_objective_closed_forms():
 
 
 def test_hinge_takes_zero_slope_exactly_at_the_kink():
-    """The paper names hinge loss without choosing a subgradient at y*yhat == 1; this build
+    """The paper names hinge loss without choosing a subgradient at y*yhat == 1; the implementation
     takes 0 there (the step fires only on strict inequality)."""
     X = np.array([[1.0, 0.0]], dtype=np.float32)
     y = np.array([1.0], dtype=np.float32)
