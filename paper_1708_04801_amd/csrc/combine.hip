@@ -13,13 +13,13 @@ namespace wpsgd {
 
 constexpr int kCombineThreads = 256;
 
-template <int VEC, int RS>
-__global__ __launch_bounds__(kCombineThreads) __attribute__((amdgpu_waves_per_eu(6))) void combine_kernel(const float *__restrict__ W,
+template <int VEC, int RS, int THREADS = kCombineThreads>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(6))) void combine_kernel(const float *__restrict__ W,
                                                                   const double *__restrict__ a,
                                                                   int k, int64_t d,
                                                                   float *__restrict__ out)
 {
-    constexpr int CT = kCombineThreads / RS;          // column-owning threads per workgroup
+    constexpr int CT = THREADS / RS;                  // column-owning threads per workgroup
     constexpr int UNROLL = 16;                        // rows requested before the first is used
     constexpr int TAIL = 4;                           // the same for the rows left over
     __shared__ double part[RS][CT][VEC];
@@ -115,6 +115,14 @@ static hipError_t launch_combine_vec(const float *W, const double *a, int k, int
     int rs = 1;
     if (col_threads < 256 * 1024 && k >= 64) rs = 4;
     if (col_threads < 64 * 1024 && k >= 256) rs = 16;
+    // Very few columns, very many rows (2048 chains of 256 columns): 1024 threads, 64 slices of the
+    // rows per workgroup, so that a thread walks 32 rows instead of 128 (one dependent batch of
+    // loads instead of eight).
+    if (col_threads <= 1024 && k >= 1024) {
+        const unsigned grid64 = (unsigned)((col_threads + 15) / 16);
+        hipLaunchKernelGGL((combine_kernel<VEC, 64, 1024>), dim3(grid64), dim3(1024), 0, s, W, a, k, d, out);
+        return hipGetLastError();
+    }
     const int ct = kCombineThreads / rs;
     const unsigned grid = (unsigned)((col_threads + ct - 1) / ct);
     if (rs == 1)
