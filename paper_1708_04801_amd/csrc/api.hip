@@ -1,6 +1,7 @@
 // The C ABI of libwpsgd (see wpsgd.h): argument checks, the kernel planner, the host-side
 // weights of Eq. 6 / Eq. 8, and the small host->device hand-overs the kernels need.
 #include <algorithm>
+#include <atomic>
 #include <climits>
 #include <cmath>
 #include <cstdio>
@@ -75,7 +76,8 @@ static int dense_vec(const wpsgd_matrix *X)
 // some instantiated shape holds d elements, else to the HBM-state kernel.
 static int compute_units()
 {
-    static int cus = 0;
+    static std::atomic<int> cached{0};          // (asking twice is harmless)
+    int cus = cached.load(std::memory_order_relaxed);
     if (cus == 0) {
         int dev = 0, n = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
@@ -83,6 +85,7 @@ static int compute_units()
             return 256;                 // no device to ask (planning on a host without one): the target's count
         }
         cus = n;
+        cached.store(cus, std::memory_order_relaxed);
     }
     return cus;
 }

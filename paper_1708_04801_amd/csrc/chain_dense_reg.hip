@@ -29,6 +29,8 @@
 // for one workgroup runs as several, each with NT*EPT columns, that add their sums once per round.
 //
 // This file is compiled once per (row storage, loss) pair; WPSGD_TX_BF16 and WPSGD_LOSS select it.
+#include <atomic>
+
 #include "dense_rows.h"
 #include "chain_dense_wide.h"
 #include "chain_dense_fed.h"
@@ -535,13 +537,15 @@ static void launch_variant(const ChainArgs &a, hipStream_t s)
         size_t claim = 0;
         if (a.helpers > 0) {
             // more than half of a compute unit's LDS per workgroup: chains and helpers each get a unit of their own
-            static int allowed = 0;         // 0 not asked yet, 1 granted, -1 refused
-            if (allowed == 0) {
-                allowed = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, 84 * 1024) == hipSuccess ? 1 : -1;
-                if (allowed < 0) (void)hipGetLastError();
+            static std::atomic<int> allowed{0};         // 0 not asked yet, 1 granted, -1 refused (asking twice is harmless)
+            int may = allowed.load(std::memory_order_relaxed);
+            if (may == 0) {
+                may = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 84 * 1024) == hipSuccess ? 1 : -1;
+                if (may < 0) (void)hipGetLastError();
+                allowed.store(may, std::memory_order_relaxed);
             }
-            if (allowed > 0) claim = 84 * 1024;
+            if (may > 0) claim = 84 * 1024;
         }
         ChainArgs b = a;
         if (claim == 0) b.helpers = 0;

@@ -7,6 +7,8 @@
 // row's loss to its own running total.  Which rows a wave takes, and the order in which the
 // waves' totals are added, are fixed by the launch shape, so the result does not depend on
 // timing.  The model vector is read through the cache hierarchy (it is at most a few MiB).
+#include <atomic>
+
 #include "device_utils.h"
 #include "internal.h"
 
@@ -189,7 +191,8 @@ __global__ __launch_bounds__(kFinishThreads) void objective_finish_kernel(const 
 template <auto kernel>
 unsigned resident_grid(unsigned most)
 {
-    static unsigned resident = 0;        // (one instance per kernel)
+    static std::atomic<unsigned> cached{0};        // (one instance per kernel; working it out twice is harmless)
+    unsigned resident = cached.load(std::memory_order_relaxed);
     if (resident == 0) {
         // a workgroup is one wave on each of a compute unit's four SIMDs; a SIMD has 512 registers
         // per lane, handed out in blocks of eight, and room for eight waves
@@ -203,6 +206,7 @@ unsigned resident_grid(unsigned most)
         const int blocks = (attr.numRegs + 7) / 8 * 8;
         const int per_cu = blocks >= 512 ? 1 : (512 / blocks < 8 ? 512 / blocks : 8);
         resident = (unsigned)per_cu * (unsigned)cus;
+        cached.store(resident, std::memory_order_relaxed);
     }
     return resident < most ? resident : most;
 }

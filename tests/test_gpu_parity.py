@@ -622,6 +622,46 @@ def test_calls_on_side_streams_match_the_default_stream():
     check_against_oracle(cases[0], got[0][0], label="side stream")
 
 
+def test_two_host_threads_call_the_library_at_once():
+    """The staging buffers for host arrays belong to the calling thread: two threads, each on a stream
+    of its own, run the whole path side by side many times and get the single-threaded bits."""
+    import threading
+    rng = np.random.default_rng(45)
+    m, d = 256, 512
+    X = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    cases = [wl.Workload("thread_a", wl.LOGISTIC, 0.5, 1e-2, 3, np.array([120, 60, 90, 7, 33], dtype=np.int64), y, m, d, dense=X),
+             wl.Workload("thread_b", wl.HINGE, 0.1, 1e-3, 4, np.array([64, 100, 17], dtype=np.int64), y, m, d, dense=X)]
+    Xg, yg = api.matrix_from_workload(cases[0]), torch.from_numpy(y).cuda()
+
+    def whole_path(w, stream=None):
+        W = api.wpsgd_run_chains(Xg, yg, w.n_steps, w.eta, w.lam, w.loss, w.seed, stream=stream)
+        return api.wpsgd_combine(W, api.wpsgd_weights(w.n_steps, w.eta, w.lam), stream=stream)
+
+    want = [whole_path(w).clone() for w in cases]
+    torch.cuda.synchronize()
+    wrong, errors = [0, 0], []
+
+    def worker(i):
+        try:
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                for _ in range(40):
+                    got = whole_path(cases[i], stream=st)
+                    st.synchronize()
+                    wrong[i] += int(not torch.equal(got, want[i]))
+        except Exception as e:           # (an assertion in a thread would otherwise go unseen)
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert wrong == [0, 0]
+
+
 # ------------------------------------------------------------------ random shapes and plans
 
 def _random_case(rng):
