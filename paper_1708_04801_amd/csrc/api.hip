@@ -593,8 +593,14 @@ int wpsgd_run_spans(const wpsgd_matrix *X, const float *y, int k, const int64_t 
         rc = wpsgd_run_chains_from(X, y, k, steps_per_span, eta, lambda, loss, seed, sampling, sp == 0 ? w_start : w_out,
                                    first.data(), W, ws + models, chains, plan, stream);
         if (rc != WPSGD_OK) return rc;
-        rc = wpsgd_combine(W, a.data(), k, X->d, w_out, ws + models + chains, average, stream);
-        if (rc != WPSGD_OK) return rc;
+        if (sp == 0) {          // (this call also carries the weights to the device; they stay there for the spans to come)
+            rc = wpsgd_combine(W, a.data(), k, X->d, w_out, ws + models + chains, average, stream);
+            if (rc != WPSGD_OK) return rc;
+        } else {
+            hipError_t e = launch_combine(W, reinterpret_cast<const double *>(ws + models + chains), k, X->d, w_out,
+                                          static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) return hip_fail(e);
+        }
     }
     return WPSGD_OK;
 }
