@@ -59,10 +59,11 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     constexpr int NG = B * (B - 1) / 2;
     constexpr int NR = B + NG;
     // independent partial sums per dot product: enough chains of dependent FMAs in flight to hide their
-    // latency.  A round of two or more steps forms three or more sums side by side, so two each will do
-    // (and six additions fewer per round than with four: 2.5 % of a round at d = 4096; sliced chains of
-    // 128 KiB rows showed no difference and keep four).
-    constexpr int NACC = EPT < 4 ? EPT : (NR >= 3 && !SLICED ? 2 : 4);
+    // latency.  A round of two or more steps forms three or more sums side by side, which are chains
+    // enough: one accumulator each (nine additions fewer per round than with four: 4.5 % of a round at
+    // d = 4096, where two accumulators gave 2.5 %; sliced chains of 128 KiB rows showed no difference
+    // and keep four).
+    constexpr int NACC = EPT < 4 ? EPT : (NR >= 3 && !SLICED ? 1 : 4);
     constexpr int D = B * P;                       // steps per group of P rounds
     static_assert(kWave % D == 0, "a 64-step window must hold whole groups");
     __shared__ TV red[2][NR][NW];
