@@ -82,8 +82,7 @@ typedef struct wpsgd_plan {
     int rows;            /* where a dense row waits between its dot product and its update:
                             1 registers, requested `prefetch` rounds ahead; 2 registers, with the next
                             row landing in LDS meanwhile (rows up to 128 KiB); 3 nowhere: the row is
-                            streamed twice (rows too long for 1 and 2); 4 registers, copied from a ring of
-                            LDS slots that waves of their own fill from HBM (256 worker threads)       */
+                            streamed twice (rows too long for 1 and 2)                                 */
     int helpers;         /* dense, 256 threads, k a multiple of 8: workgroups per chain that run ahead of
                             it on otherwise idle compute units and pull its rows into the L2 cache the
                             chain's compute unit shares.  0: choose (2 when compute units are to spare

@@ -22,7 +22,7 @@
  * [0, m) by multiply-shift.  Both sides implement it from the published
  * definition.
  *
- * Parity pins live in tests/test_oracle_*.py (known-answer Philox vectors,
+ * Parity pins live in tests/test_oracle_pins.py (known-answer Philox vectors,
  * hand-computed weights, closed forms of the SGD recursion, finite-difference
  * gradient checks, brute force).  Parity unpinned: nothing in this file.
  *

@@ -163,8 +163,15 @@ def _steps(n_steps):
     return np.ascontiguousarray(np.asarray(n_steps), dtype=np.int64)
 
 
-def _workspace(nbytes, device):
-    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+def _workspace(nbytes, device, stream=None):
+    """A temporary workspace for one call.  It is allocated on torch's current stream; when the call's
+    work is queued on another stream the caching allocator is told so, or it could hand the block to
+    later current-stream work while that stream still uses it."""
+    t = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+    if stream is not None:
+        with torch.cuda.device(t.device):
+            t.record_stream(stream if isinstance(stream, torch.cuda.Stream) else torch.cuda.ExternalStream(int(stream)))
+    return t
 
 
 def wpsgd_describe_plan(X: Matrix, k, loss, plan=None) -> str:
@@ -196,7 +203,7 @@ def wpsgd_run_chains(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
     pl = _plan(plan)
     if workspace is None:
         need = load().wpsgd_run_chains_workspace(ctypes.byref(cm), k, int(loss), pl)
-        workspace = _workspace(need, dev)
+        workspace = _workspace(need, dev, stream)
     rc = load().wpsgd_run_chains(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, float(eta),
                                  float(lam), int(loss), int(seed), W.data_ptr(),
                                  workspace.data_ptr(), workspace.numel(), pl, _stream(stream))
@@ -228,7 +235,7 @@ def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, s
     pl = _plan(plan)
     if workspace is None:
         need = load().wpsgd_run_chains_workspace(ctypes.byref(cm), k, int(loss), pl)
-        workspace = _workspace(need, dev)
+        workspace = _workspace(need, dev, stream)
     rc = load().wpsgd_run_chains_from(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, float(eta),
                                       float(lam), int(loss), int(seed), int(sampling),
                                       w_start.data_ptr() if w_start is not None else None,
@@ -257,7 +264,7 @@ def wpsgd_run_spans(X: Matrix, y: torch.Tensor, steps_per_span, n_spans, eta, la
     pl = _plan(plan)
     if workspace is None:
         need = load().wpsgd_run_spans_workspace(ctypes.byref(cm), k, int(loss), pl)
-        workspace = _workspace(need, dev)
+        workspace = _workspace(need, dev, stream)
     rc = load().wpsgd_run_spans(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, int(n_spans), float(eta),
                                 float(lam), int(loss), int(seed), int(sampling),
                                 w_start.data_ptr() if w_start is not None else None, w_out.data_ptr(),
@@ -318,7 +325,7 @@ def wpsgd_combine(W: torch.Tensor, a, w_out: Optional[torch.Tensor] = None,
     if w_out is None:
         w_out = torch.empty(d, dtype=torch.float32, device=W.device)
     if workspace is None:
-        workspace = _workspace(wpsgd_combine_workspace(k, d), W.device)
+        workspace = _workspace(wpsgd_combine_workspace(k, d), W.device, stream)
     rc = load().wpsgd_combine(W.data_ptr(), a.ctypes.data, k, d, w_out.data_ptr(),
                               workspace.data_ptr(), workspace.numel(), _stream(stream))
     if rc != OK:
@@ -340,7 +347,7 @@ def wpsgd_objective(X: Matrix, y: torch.Tensor, w: torch.Tensor, lam, loss, out:
     if out is None:
         out = torch.empty(2, dtype=torch.float64, device=y.device)
     if workspace is None:
-        workspace = _workspace(wpsgd_objective_workspace(X), y.device)
+        workspace = _workspace(wpsgd_objective_workspace(X), y.device, stream)
     rc = load().wpsgd_objective(ctypes.byref(cm), y.data_ptr(), w.data_ptr(), float(lam), int(loss), out.data_ptr(),
                                 workspace.data_ptr(), workspace.numel(), _stream(stream))
     if rc != OK:

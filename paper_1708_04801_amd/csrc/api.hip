@@ -98,7 +98,7 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     p.dtype = X->dense ? (int)X->dtype : WPSGD_F32;
     const size_t state_elem = (loss == WPSGD_HINGE) ? sizeof(double) : sizeof(float);
     const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0, 0, 0, 0};
-    if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0 || f.rows < 0 || f.rows > 4 || f.helpers < -1 || f.helpers > 3 || f.slices < 0 || f.slices > 8) return WPSGD_INVALID_ARG;
+    if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0 || f.rows < 0 || f.rows > 3 || f.helpers < -1 || f.helpers > 3 || f.slices < 0 || f.slices > 8) return WPSGD_INVALID_ARG;
 
     if (!X->dense) {
         if (f.threads && f.threads != kWave && f.threads != 2 * kWave) return WPSGD_UNSUPPORTED;
@@ -242,11 +242,15 @@ static size_t header_bytes(int k)
            align256((size_t)k * 3 * sizeof(uint32_t)) + align256(((size_t)k * 2 + 16) * sizeof(uint32_t)) + kPowTabBytes;
 }
 
+// 32-bit words of the table the column slices of k chains exchange their sums through: per chain
+// 8 slices x 2 round parities x 32 words of records, then 8 words (the slices' XCD numbers)
+static size_t slice_table_words(int k) { return (size_t)k * (8 * 2 * 32 + 8); }
+
 // Helper workgroups per chain for a resolved plan: only the 256-thread register kernels have
 // them, and only on compute units no chain occupies (at most 128 chains).
 static int helpers_per_chain(const Plan &p, const wpsgd_matrix *X, int k, const wpsgd_plan *force)
 {
-    if (p.family != Family::DenseReg || p.threads != 256 || (p.rows != 1 && p.rows != 4) || k > 128 || p.slices > 1) return 0;
+    if (p.family != Family::DenseReg || p.threads != 256 || p.rows != 1 || k > 128 || p.slices > 1) return 0;
     const int asked = force ? force->helpers : 0;
     if (asked < 0) return 0;
     const int room = (compute_units() - k) / k;
@@ -265,13 +269,33 @@ struct StagingSlot {
     bool pending = false;
 };
 constexpr int kStagingSlots = 4;     // copies that may be queued before a call has to wait
-static thread_local StagingSlot g_staging[kStagingSlots];
-static thread_local int g_staging_next = 0;
+struct StagingRing {
+    StagingSlot slot[kStagingSlots];
+    int next = 0;
+    // A host thread that ends gives its buffers back (once their last copies have finished).  If the
+    // runtime is already shutting down the calls fail and the process's exit reclaims everything.
+    ~StagingRing()
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return;
+        }
+        for (StagingSlot &st : slot) {
+            if (st.pending && st.last_copy) (void)hipEventSynchronize(st.last_copy);
+            if (st.last_copy) (void)hipEventDestroy(st.last_copy);
+            if (st.host) (void)hipHostFree(st.host);
+            st = StagingSlot{};
+        }
+        (void)hipGetLastError();
+    }
+};
+static thread_local StagingRing g_staging;
 
 static int upload(void *dst, const void *src, size_t bytes, hipStream_t s)
 {
-    StagingSlot &st = g_staging[g_staging_next];
-    g_staging_next = (g_staging_next + 1) % kStagingSlots;
+    StagingSlot &st = g_staging.slot[g_staging.next];
+    g_staging.next = (g_staging.next + 1) % kStagingSlots;
     hipError_t e;
     if (st.pending) {
         e = hipEventSynchronize(st.last_copy);
@@ -344,7 +368,7 @@ int wpsgd_describe_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     Plan p;
     rc = resolve_plan(X, k, loss, plan, &p);
     if (rc != WPSGD_OK) return rc;
-    static const char *const kRows[] = {"", " rows=registers", " rows=lds", " rows=twice", " rows=fed"};
+    static const char *const kRows[] = {"", " rows=registers", " rows=lds", " rows=twice"};
     char helped[32] = "";
     const int hp = helpers_per_chain(p, X, k, plan);
     if (hp > 0) std::snprintf(helped, sizeof(helped), " helpers=%d", hp);
@@ -388,7 +412,11 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     for (int i = 0; i < k; ++i) max_steps = std::max(max_steps, n_steps[i]);
     rc = resolve_plan(X, k, loss, plan, &p, 1.0 - eta * lambda, max_steps);
     if (rc != WPSGD_OK) return rc;
-    const size_t need = header_bytes(k) + perm_bytes(X->m) + align256((size_t)k * (size_t)X->d * p.state_bytes_per_elem);
+    // behind the header and the shuffled order: the model vectors of the HBM-state kernels, or the
+    // table the column slices of a chain exchange their sums through
+    const bool sliced = p.family == Family::DenseReg && p.slices > 1;
+    const size_t behind = sliced ? slice_table_words(k) * sizeof(uint32_t) : (size_t)k * (size_t)X->d * p.state_bytes_per_elem;
+    const size_t need = header_bytes(k) + perm_bytes(X->m) + align256(behind);
     if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
     if (workspace_bytes < need) return WPSGD_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -455,10 +483,10 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     a.pow_tab = reinterpret_cast<const double *>(ws + header_bytes(k) - kPowTabBytes);
     a.progress = reinterpret_cast<uint32_t *>(ws + order_bytes + 2 * steps_bytes + align256((size_t)k * 3 * sizeof(uint32_t)));
     a.helpers = helpers_per_chain(p, X, k, plan) * k;
-    a.slices = p.family == Family::DenseReg && p.slices > 1 ? p.slices : 1;
+    a.slices = sliced ? p.slices : 1;
     a.xchg = state_dev;
     if (a.slices > 1) {
-        hipError_t ze = launch_zero_words(static_cast<uint32_t *>(state_dev), (size_t)k * (8 * 2 * 32 + 8), s);
+        hipError_t ze = launch_zero_words(static_cast<uint32_t *>(state_dev), slice_table_words(k), s);
         if (ze != hipSuccess) return hip_fail(ze);
     }
     a.eta = eta;

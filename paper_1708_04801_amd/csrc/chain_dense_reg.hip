@@ -33,7 +33,6 @@
 
 #include "dense_rows.h"
 #include "chain_dense_wide.h"
-#include "chain_dense_fed.h"
 
 namespace wpsgd {
 
@@ -475,7 +474,7 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
 // (threads, ept, vec) shape the first entry is the default; the others are reachable through a
 // forced plan.  Register budget per thread: 512 at 256 threads, 256 at 512, 128 at 1024.
 // P > 0: rows wait in registers, P rounds requested ahead.  P = -1: the next row is staged in LDS.
-// P = 0: rows are streamed twice.  P = -2: rows are fed through an LDS ring by mover waves.
+// P = 0: rows are streamed twice.
 // ---------------------------------------------------------------------------------------------
 // 64 elements per thread only with fp32 state (logistic): 64 fp64 values would fill the registers
 #if WPSGD_LOSS == 1
@@ -500,8 +499,6 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     V(256, 8, 8, 4, 2) V(256, 16, 8, 4, 2)                                                     \
     V(256, 8, 8, 2, 4) V(256, 16, 8, 2, 4) V(256, 32, 8, 2, 4) V(256, 64, 8, 2, 2) V(256, 64, 8, 1, 4) \
     V(256, 64, 8, 4, 2)                                                                        \
-    V(256, 8, 8, 1, -2) V(256, 16, 8, 1, -2) V(256, 32, 8, 1, -2)                              \
-    V(256, 8, 8, 2, -2) V(256, 16, 8, 2, -2) V(256, 32, 8, 2, -2)                              \
     V(1024, 16, 8, 1, -1) V(1024, 32, 8, 1, -1) WPSGD_WIDEST_LDS(V, 8)                          \
     V(1024, 16, 8, 1, 0) V(1024, 32, 8, 1, 0) WPSGD_WIDEST(V, 8)
 #define WPSGD_VARIANTS_WIDE(V)
@@ -512,8 +509,6 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     V(256, 4, 4, 4, 2) V(256, 8, 4, 4, 2) V(256, 16, 4, 4, 2) V(256, 16, 4, 1, 4)              \
     V(256, 16, 4, 2, 2) V(256, 16, 4, 2, 4) V(256, 16, 4, 2, 8) V(256, 32, 4, 4, 2)            \
     V(256, 4, 4, 2, 4) V(256, 8, 4, 2, 4) V(256, 32, 4, 2, 2)                                  \
-    V(256, 4, 4, 1, -2) V(256, 8, 4, 1, -2) V(256, 16, 4, 1, -2) V(256, 32, 4, 1, -2)          \
-    V(256, 4, 4, 2, -2) V(256, 8, 4, 2, -2) V(256, 16, 4, 2, -2)                               \
     V(512, 8, 4, 1, 8) V(512, 8, 4, 4, 2) V(512, 8, 4, 2, 4)                                   \
     V(1024, 4, 4, 1, 8) V(1024, 4, 4, 4, 2) V(1024, 4, 4, 2, 4)                                \
     V(1024, 16, 4, 1, -1) V(1024, 32, 4, 1, -1)                                                \
@@ -534,10 +529,7 @@ constexpr bool can_slice(int nt, int vec, int bb, int pp)
 template <int NT, int EPT, int VEC, int BB, int PP>
 static void launch_variant(const ChainArgs &a, hipStream_t s)
 {
-    if constexpr (PP == -2) {
-        // (its LDS ring leaves room for one workgroup per compute unit, helpers included)
-        hipLaunchKernelGGL((chain_dense_fed_kernel<RowElem, kLoss, NT, EPT, VEC, BB>), dim3(a.k + a.helpers), dim3(2 * NT), 0, s, a);
-    } else if constexpr (PP < 0) {
+    if constexpr (PP < 0) {
         hipLaunchKernelGGL((chain_dense_lds_kernel<RowElem, kLoss, NT, EPT, VEC>), dim3(a.k), dim3(NT), 0, s, a);
     } else if constexpr (PP == 0) {
         hipLaunchKernelGGL((chain_dense_wide_kernel<RowElem, kLoss, NT, EPT, VEC>), dim3(a.k), dim3(NT), 0, s, a);
@@ -576,7 +568,7 @@ static void launch_variant(const ChainArgs &a, hipStream_t s)
 #define WPSGD_SUFFIX WPSGD_CAT(f32_loss, WPSGD_LOSS)
 #endif
 
-constexpr int rows_kind(int pp) { return pp > 0 ? 1 : (pp == -1 ? 2 : (pp == 0 ? 3 : 4)); }
+constexpr int rows_kind(int pp) { return pp > 0 ? 1 : (pp == -1 ? 2 : 3); }
 
 // find(plan, launch?): walks the table; exact match on (threads, ept, vec, B, P, rows) where the
 // plan gives them, else the first entry of the shape.

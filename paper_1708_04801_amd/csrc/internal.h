@@ -62,8 +62,7 @@ struct Plan {
     int vec;         // elements per global load instruction
     int block_steps; // B
     int prefetch;    // P: rounds in flight
-    int rows;        // DenseReg: 1 rows wait in registers, 2 next row staged in LDS, 3 rows streamed twice,
-                     // 4 rows fed through an LDS ring by mover waves
+    int rows;        // DenseReg: 1 rows wait in registers, 2 next row staged in LDS, 3 rows streamed twice
     int slices;      // DenseReg, rows = 1: workgroups (column slices) per chain
     size_t state_bytes_per_elem;   // 0 when the state lives in registers
 };

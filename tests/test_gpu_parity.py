@@ -8,7 +8,7 @@ Bars (fp32 GPU output against the fp64 oracle):
     exempted from the per-chain check (the branch there is decided by rounding), never from the
     check of the final model.
 Small cases cover every kernel family and forced plan, ragged and unaligned shapes, idle
-chains, heavy shrink; the five full-size workloads are checked on sampled chains.
+chains, heavy shrink; the five full-size workloads compare every chain and the final model.
 """
 import math
 
@@ -43,11 +43,13 @@ def gpu_chains(w, plan=None, X=None, y=None):
     return W
 
 
-def check_against_oracle(w, W_gpu, chain_ids=None, label=""):
-    """Per-chain and final-model parity; chain_ids selects the chains the oracle computes."""
+def check_against_oracle(w, W_gpu, chain_ids=None, label="", csr_mode=orc.PLAIN):
+    """Per-chain and final-model parity; chain_ids selects the chains the oracle computes.
+    csr_mode = orc.LAZY runs sparse chains in the oracle's scalar-scale mode (pinned to the literal
+    shrink at 1e-12 by the CPU tests), for matrices so wide that the literal shrink takes minutes."""
     ids = np.arange(w.k) if chain_ids is None else np.asarray(chain_ids)
     Wo, margin = orc.run_chains(oracle_matrix(w), w.y, w.n_steps, w.eta, w.lam, w.loss, w.seed,
-                                chain_ids=ids)
+                                chain_ids=ids, csr_mode=csr_mode)
     Wg = W_gpu[torch.from_numpy(ids).cuda()].cpu().numpy()
     assert np.isfinite(Wg).all(), f"{label}: non-finite model"
     errs = np.array([rel_l2(Wg[q], Wo[q]) for q in range(ids.size)])
@@ -133,11 +135,6 @@ DENSE_PLANS = [
     (12000, wl.LOGISTIC, {"rows": 3}), (16384, wl.HINGE, {"rows": 3}), (20000, wl.LOGISTIC, {"rows": 3}),
     (20000, wl.HINGE, {"rows": 2}), (32768, wl.LOGISTIC, {"rows": 2}), (32768, wl.HINGE, None),
     (40000, wl.LOGISTIC, None),
-    # rows brought in by mover waves through an LDS ring
-    (4096, wl.LOGISTIC, {"rows": 4}), (4096, wl.HINGE, {"rows": 4}), (4096, wl.LOGISTIC, {"rows": 4, "block_steps": 2}),
-    (4096, wl.HINGE, {"rows": 4, "block_steps": 2}), (1000, wl.LOGISTIC, {"rows": 4}), (3000, wl.HINGE, {"rows": 4}),
-    (2048, wl.LOGISTIC, {"rows": 4, "block_steps": 2}), (1500, wl.HINGE, {"rows": 4, "block_steps": 2}),
-    (8192, wl.HINGE, {"rows": 4}), (8000, wl.LOGISTIC, {"rows": 4}), (260, wl.LOGISTIC, {"rows": 4}),
 ]
 
 
@@ -153,7 +150,7 @@ def test_dense_fp32_chains(d, loss, plan):
     Xg = api.matrix_from_workload(w)
     desc = api.wpsgd_describe_plan(Xg, k, loss, plan)
     if plan and "rows" in plan:
-        assert {2: "rows=lds", 3: "rows=twice", 4: "rows=fed"}[plan["rows"]] in desc
+        assert {2: "rows=lds", 3: "rows=twice"}[plan["rows"]] in desc
     W = gpu_chains(w, plan=plan, X=Xg)
     check_against_oracle(w, W, label=f"d={d} [{desc}]")
     assert (W[2] == 0).all()                                     # idle chain keeps w_0 = 0
@@ -163,8 +160,7 @@ def test_dense_fp32_chains(d, loss, plan):
 
 @pytest.mark.parametrize("k,d,helpers,extra", [
     (8, 4096, 3, {}), (16, 4096, 1, {}), (8, 2048, 2, {}), (24, 8192, 0, {}), (8, 1000, 3, {}),
-    (8, 4096, 3, {"rows": 4}), (16, 2048, 2, {"rows": 4, "block_steps": 2}), (8, 8192, 0, {"rows": 4}),
-    (9, 4096, 2, {}), (13, 4096, 3, {"block_steps": 1}), (70, 2048, 1, {}), (3, 4096, 3, {"rows": 4})])
+    (9, 4096, 2, {}), (13, 4096, 3, {"block_steps": 1}), (70, 2048, 1, {}), (3, 4096, 3, {"block_steps": 2})])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
 def test_dense_chains_with_helper_workgroups(k, d, helpers, extra, loss):
     """Workgroups that run ahead of the chains and pull their rows into L2 change when a row arrives,
@@ -222,9 +218,7 @@ def test_dense_chains_cut_into_column_slices(d, bf16, loss, plan):
 BF16_PLANS = [(64, None), (256, None), (512, None), (520, None), (2048, {"block_steps": 4}), (4096, None),
               (8192, {"block_steps": 1}), (16384, None), (30000, None), (65536, None),
               (65536, {"state_in_hbm": 1}), (4100, {"state_in_hbm": 1}), (40000, None), (33000, None),
-              (16384, {"rows": 3}), (30000, {"rows": 3}), (12000, {"rows": 2}),
-              (4096, {"rows": 4}), (2048, {"rows": 4, "block_steps": 2}), (8192, {"rows": 4}), (8000, {"rows": 4}),
-              (1032, {"rows": 4, "block_steps": 2})]
+              (16384, {"rows": 3}), (30000, {"rows": 3}), (12000, {"rows": 2})]
 
 
 @pytest.mark.parametrize("d,plan", BF16_PLANS)
@@ -479,8 +473,7 @@ def _check_from(w, plan, label):
 
 
 @pytest.mark.parametrize("d,plan", [(64, None), (300, None), (4096, None), (4096, {"block_steps": 4}),
-                                    (5000, {"state_in_hbm": 1}), (20000, None), (20000, {"rows": 3}),
-                                    (4096, {"rows": 4}), (2000, {"rows": 4, "block_steps": 2})])
+                                    (5000, {"state_in_hbm": 1}), (20000, None), (20000, {"rows": 3})])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
 def test_dense_chains_from_a_start_vector_and_stream_offsets(d, plan, loss):
     rng = np.random.default_rng(d + 3 * loss)
@@ -688,7 +681,7 @@ def _random_case(rng):
         elif r < 0.30:
             plan = {"helpers": int(rng.choice([1, 2, 3]))}
         elif r < 0.35:
-            plan = {"rows": 4}
+            plan = {"helpers": -1}
         elif r < 0.40:
             plan = {"state_in_hbm": 1}
     y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
@@ -768,7 +761,7 @@ def _check_shards(w, plan, label):
 
 
 @pytest.mark.parametrize("d,plan", [(64, None), (300, None), (4096, None), (5000, {"state_in_hbm": 1}), (20000, None),
-                                    (20000, {"rows": 3}), (4096, {"rows": 4}), (2000, {"rows": 4, "block_steps": 2})])
+                                    (20000, {"rows": 3})])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
 def test_dense_chains_on_shuffled_shards(d, plan, loss):
     rng = np.random.default_rng(d + 5 * loss)
@@ -781,7 +774,7 @@ def test_dense_chains_on_shuffled_shards(d, plan, loss):
 
 
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
-@pytest.mark.parametrize("plan", [{"threads": 256, "helpers": 2}, {"threads": 256, "helpers": 1, "rows": 4}])
+@pytest.mark.parametrize("plan", [{"threads": 256, "helpers": 2}, {"threads": 256, "helpers": 1, "block_steps": 1}])
 def test_helped_chains_from_offsets_and_on_shards(plan, loss):
     """Helper workgroups walk the same sample stream as their chain under every sampling mode:
     a start vector with per-chain stream offsets, and partition-and-shuffle sampling."""
@@ -926,24 +919,6 @@ def test_run_chains_rejects_bad_arguments():
 
 # ------------------------------------------------------------------ the five workloads at full size
 
-def _sampled(k, count, n_steps):
-    """Chains the oracle recomputes: the longest, the shortest, and a seeded spread."""
-    rng = np.random.default_rng(99)
-    pick = {int(np.argmax(n_steps)), int(np.argmin(n_steps))}
-    pick.update(rng.choice(k, size=min(k, count), replace=False).tolist())
-    return np.array(sorted(pick))
-
-
-def _final_model_columns(w, W_gpu, cols):
-    """Final weighted model on sampled columns, recomputed in fp64 from the GPU's chain outputs."""
-    a = api.wpsgd_weights(w.n_steps, w.eta, w.lam)
-    v = api.wpsgd_combine(W_gpu, a)
-    torch.cuda.synchronize()
-    sub = W_gpu[:, torch.from_numpy(cols).cuda()].cpu().numpy().astype(np.float64)
-    np.testing.assert_allclose(v[torch.from_numpy(cols).cuda()].cpu().numpy(), a @ sub, rtol=3e-7, atol=1e-12)
-    np.testing.assert_allclose(a, orc.weights(w.n_steps, w.eta, w.lam), rtol=1e-11)
-
-
 def test_full_dense_logistic():
     w = wl.dense_logistic()
     W = gpu_chains(w)
@@ -959,9 +934,7 @@ def test_full_many_chains():
 def test_full_wide_bf16():
     w = wl.wide_bf16()
     W = gpu_chains(w)
-    ids = _sampled(w.k, 6, w.n_steps)
-    check_against_oracle(w, W, chain_ids=ids, label="wide_bf16 full")
-    _final_model_columns(w, W, np.arange(0, w.d, 997))
+    check_against_oracle(w, W, label="wide_bf16 full")               # all 32 chains and the final model
 
 
 def test_full_sparse_hinge():
@@ -972,13 +945,6 @@ def test_full_sparse_hinge():
     by_len = np.argsort(w.n_steps)
     ids = np.array(sorted(set(by_len[:6].tolist()) | {int(by_len[w.k // 2])}))
     check_against_oracle(w, W, chain_ids=ids, label="sparse_hinge full")
-    # The longest chains are compared with the oracle's scalar-scale mode (itself pinned to the
-    # plain mode in the CPU tests).
-    long_ids = np.array(sorted(by_len[-3:].tolist()))
-    Wl, margin = orc.run_chains(oracle_matrix(w), w.y, w.n_steps, w.eta, w.lam, w.loss, w.seed,
-                                chain_ids=long_ids, csr_mode=orc.LAZY)
-    Wg = W[torch.from_numpy(long_ids).cuda()].cpu().numpy()
-    for q, i in enumerate(long_ids):
-        if margin[q] >= KINK:
-            assert rel_l2(Wg[q], Wl[q]) <= TOL, f"sparse chain {i}: {rel_l2(Wg[q], Wl[q])}"
-    _final_model_columns(w, W, np.arange(0, w.d, 4099))
+    # All 128 chains and the final model against the oracle's scalar-scale mode.
+    errs, margin = check_against_oracle(w, W, label="sparse_hinge full, every chain", csr_mode=orc.LAZY)
+    assert (margin >= KINK).all(), f"a chain came within {margin.min()} of the hinge kink"

@@ -143,7 +143,6 @@ def test_planner_picks_registers_when_the_vector_fits_and_hbm_otherwise():
     assert "helpers=1" in d(_FakeMatrix(262144, 4096), 128, api.LOGISTIC)            # one spare compute unit per chain
     assert "helpers" not in d(_FakeMatrix(262144, 4096), 129, api.LOGISTIC)
     assert "helpers" not in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"helpers": -1})
-    assert "rows=fed" in d(_FakeMatrix(262144, 4096), 64, api.LOGISTIC, plan={"rows": 4})
     # rows too long for one 256-thread workgroup and compute units to spare: column slices
     assert "ept=32 vec=8 B=2 P=4" in d(_FakeMatrix(65536, 65536, api.BF16), 32, api.LOGISTIC)
     assert "slices=8" in d(_FakeMatrix(65536, 65536, api.BF16), 32, api.LOGISTIC)

@@ -459,6 +459,38 @@ def test_chain_rows_follow_their_own_streams_and_subsets():
     assert np.array_equal(Wsub[0], W[3]) and np.array_equal(Wsub[1], W[0])
 
 
+@pytest.mark.parametrize("loss", [orc.HINGE, orc.LOGISTIC])
+def test_constant_start_value_of_the_experiments(loss):
+    """Section V starts every node from a constant vector (4 there) instead of Algorithm 1's zero.
+    With w_0 = c*1 the first step is closed-form (Eq. 5 with Eq. 4): yhat = c*sum(x_j) and
+    w_1 = (1 - eta*lambda)*c*1 - eta*g*x_j; a chain of no steps returns c*1; longer chains are the
+    sequential recursion started from c*1."""
+    X, y = _small_problem()
+    eta, lam, c = 0.05, 0.01, 4.0
+    n = [1, 0, 37, 150]
+    W, mm = orc.run_chains(X, y, n, eta, lam, loss, seed=11, w0_fill=c)
+    j = int(orc.sample_indices(11, 0, 0, 1, X.m)[0])
+    x = X.data[j].astype(np.float64)
+    yj = float(y[j])
+    yhat = c * x.sum()
+    g = (-yj if yj * yhat < 1.0 else 0.0) if loss == orc.HINGE else -yj / (1.0 + math.exp(yj * yhat))
+    np.testing.assert_allclose(W[0], (1.0 - eta * lam) * c - eta * g * x, rtol=1e-14, atol=1e-15)
+    assert (W[1] == c).all() and math.isinf(mm[1])
+    for i in (2, 3):
+        w, m_i = orc.sgd(X, y, orc.sample_indices(11, i, 0, n[i], X.m), eta, lam, loss, w0=np.full(X.d, c))
+        assert np.array_equal(W[i], w) and mm[i] == m_i
+    # the start value matters: the same chains from zero end elsewhere
+    W0, _ = orc.run_chains(X, y, n, eta, lam, loss, seed=11)
+    assert not np.allclose(W0[3], W[3])
+    # a sparse copy of the matrix, both update modes
+    rp = np.arange(0, X.m * X.d + 1, X.d, dtype=np.int64)
+    ci = np.tile(np.arange(X.d, dtype=np.int32), X.m)
+    Xs = orc.CSR(rp, ci, X.data.reshape(-1), X.d)
+    for mode in (orc.PLAIN, orc.LAZY):
+        Ws, _ = orc.run_chains(Xs, y, n, eta, lam, loss, seed=11, w0_fill=c, csr_mode=mode)
+        np.testing.assert_allclose(Ws, W, rtol=1e-12, atol=1e-14)
+
+
 def test_weighted_output_is_the_weighted_sum_of_chain_outputs():
     X, y = _small_problem()
     n = [300, 100, 200]
