@@ -198,6 +198,17 @@ size_t wpsgd_objective_workspace(const wpsgd_matrix *X);
 int wpsgd_objective(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
                     double *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The partial sums live in an area
+ * of 192 KiB that the library owns on every device it runs on (a static device array, held until
+ * the process ends), which is enough for any m; a data set that would need more is refused with
+ * WPSGD_UNSUPPORTED, as is d >= 2^29.  The call allocates nothing and the result is bit for bit
+ * that of wpsgd_objective.  All calls on one device share the area: calls that may overlap there
+ * (two streams, two host threads) race on it and must be ordered by the caller; nothing in it has
+ * to be cleared between calls.                                                                    */
+int wpsgd_objective_static(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
+                           double *out, void *stream);
+
 /* ---- sample stream (stands for the per-node shuffle and n-th-example fetch of Algorithm 1) ----
  * Row visited by chain `chain` at step n (0-based):
  *   (r0,..) = Philox4x32-10(counter = (n mod 2^32, n div 2^32, chain, 0),

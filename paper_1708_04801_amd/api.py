@@ -28,7 +28,7 @@ EXPORTS = [
     "wpsgd_sample_indices_device", "wpsgd_strerror", "wpsgd_last_hip_error", "wpsgd_describe_plan",
     "wpsgd_stream_rows", "wpsgd_objective_workspace", "wpsgd_objective",
     "wpsgd_run_chains_from", "wpsgd_shard_indices", "wpsgd_shard_indices_device",
-    "wpsgd_run_spans_workspace", "wpsgd_run_spans", "wpsgd_span_condition",
+    "wpsgd_run_spans_workspace", "wpsgd_run_spans", "wpsgd_span_condition", "wpsgd_objective_static",
 ]
 
 
@@ -93,6 +93,7 @@ def load():
     L.wpsgd_objective_workspace.argtypes = [pm]
     L.wpsgd_objective_workspace.restype = sz
     L.wpsgd_objective.argtypes = [pm, vp, vp, f64, ci, vp, vp, sz, vp]
+    L.wpsgd_objective_static.argtypes = [pm, vp, vp, f64, ci, vp, vp]
     _lib = L
     return L
 
@@ -352,6 +353,21 @@ def wpsgd_objective(X: Matrix, y: torch.Tensor, w: torch.Tensor, lam, loss, out:
                                 workspace.data_ptr(), workspace.numel(), _stream(stream))
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_objective")
+    return out
+
+
+def wpsgd_objective_static(X: Matrix, y: torch.Tensor, w: torch.Tensor, lam, loss, out: torch.Tensor,
+                           stream=None) -> torch.Tensor:
+    """wpsgd_objective without a workspace: the library's own static device area holds the partial
+    sums and the call allocates nothing (`out`, two float64 on the GPU, comes from the caller)."""
+    assert y.is_cuda and y.dtype == torch.float32 and y.numel() == X.m
+    assert w.is_cuda and w.dtype == torch.float32 and w.numel() == X.d and w.is_contiguous()
+    assert out.is_cuda and out.dtype == torch.float64 and out.numel() == 2
+    cm = X.c_struct()
+    rc = load().wpsgd_objective_static(ctypes.byref(cm), y.data_ptr(), w.data_ptr(), float(lam), int(loss),
+                                       out.data_ptr(), _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_objective_static")
     return out
 
 

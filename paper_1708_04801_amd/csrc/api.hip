@@ -653,8 +653,8 @@ size_t wpsgd_objective_workspace(const wpsgd_matrix *X)
     return align256(objective_partials_bytes(X->m));
 }
 
-int wpsgd_objective(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
-                    double *out, void *workspace, size_t workspace_bytes, void *stream)
+static int objective_check(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
+                           const double *out)
 {
     int rc = check_matrix(X);
     if (rc != WPSGD_OK) return rc;
@@ -662,8 +662,12 @@ int wpsgd_objective(const wpsgd_matrix *X, const float *y, const float *w, doubl
     if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
     if ((uintptr_t)out % sizeof(double) != 0) return WPSGD_INVALID_ARG;
     if (X->d >= (1ll << 29)) return WPSGD_UNSUPPORTED;           // 32-bit byte offsets into a row and into w
-    if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
-    if (workspace_bytes < wpsgd_objective_workspace(X)) return WPSGD_WORKSPACE_TOO_SMALL;
+    return WPSGD_OK;
+}
+
+static int objective_launch(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
+                            double *out, double *partials, hipStream_t s)
+{
     ChainArgs a{};
     a.dense = X->dense;
     a.ld = X->ld;
@@ -675,9 +679,31 @@ int wpsgd_objective(const wpsgd_matrix *X, const float *y, const float *w, doubl
     a.d = X->d;
     int vec = 1;
     if (X->dense && (uintptr_t)w % 16 == 0) vec = dense_vec(X);
-    hipError_t e = launch_objective(a, X->dense ? (int)X->dtype : WPSGD_F32, vec, (int)loss, w, lambda,
-                                    static_cast<double *>(workspace), out, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_objective(a, X->dense ? (int)X->dtype : WPSGD_F32, vec, (int)loss, w, lambda, partials, out, s);
     return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
+int wpsgd_objective(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
+                    double *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = objective_check(X, y, w, lambda, loss, out);
+    if (rc != WPSGD_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
+    if (workspace_bytes < wpsgd_objective_workspace(X)) return WPSGD_WORKSPACE_TOO_SMALL;
+    return objective_launch(X, y, w, lambda, loss, out, static_cast<double *>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int wpsgd_objective_static(const wpsgd_matrix *X, const float *y, const float *w, double lambda, wpsgd_loss loss,
+                           double *out, void *stream)
+{
+    int rc = objective_check(X, y, w, lambda, loss, out);
+    if (rc != WPSGD_OK) return rc;
+    double *partials = nullptr;          // the library's own area on this device, in place of a workspace
+    size_t room = 0;
+    hipError_t e = objective_static_partials(&partials, &room);
+    if (e != hipSuccess) return hip_fail(e);
+    if (objective_partials_bytes(X->m) > room) return WPSGD_UNSUPPORTED;     // more partial sums than that area holds
+    return objective_launch(X, y, w, lambda, loss, out, partials, static_cast<hipStream_t>(stream));
 }
 
 int wpsgd_sample_indices(uint64_t seed, int chain, int64_t n0, int64_t count, int64_t m,

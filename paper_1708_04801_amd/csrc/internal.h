@@ -83,6 +83,8 @@ hipError_t launch_stream_rows(const void *X, int64_t row_stride, uint32_t row_by
 // Objective / error-rate evaluator: ChainArgs carries the matrix, the labels and m, d only.
 int64_t objective_grid(int64_t m);
 size_t objective_partials_bytes(int64_t m);
+// the library's own partial-sum area on the current device (a file-scope device array) and its size
+hipError_t objective_static_partials(double **partials, size_t *bytes);
 hipError_t launch_objective(const ChainArgs &a, int dtype, int vec, int loss, const float *w, double lambda,
                             double *partials, double *out, hipStream_t s);
 hipError_t launch_permute_rows(uint32_t seed_lo, uint32_t seed_hi, uint32_t m, uint32_t *perm, hipStream_t s);

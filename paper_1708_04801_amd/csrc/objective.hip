@@ -236,6 +236,33 @@ int64_t objective_grid(int64_t m)
 
 size_t objective_partials_bytes(int64_t m) { return (size_t)objective_grid(m) * kObjWaves * 3 * sizeof(double); }
 
+// Partial sums for callers that cannot allocate (wpsgd_objective_static): room for the largest launch,
+// 2048 workgroups of four waves with three sums each - 192 KiB that every device the library runs
+// on holds until the process ends.  Host code never uses the array's name as an address: it asks for
+// the device address once per device and passes that to the kernels, as it passes a workspace.
+constexpr size_t kStaticPartials = (size_t)2048 * kObjWaves * 3;
+static __device__ __align__(256) double scratch[kStaticPartials];
+
+hipError_t objective_static_partials(double **partials, size_t *bytes)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<double *> address[kMaxDevices];      // (two threads asking at once get the same answer)
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    double *p = address[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        address[dev].store(p, std::memory_order_release);
+    }
+    *partials = p;
+    *bytes = kStaticPartials * sizeof(double);
+    return hipSuccess;
+}
+
 hipError_t launch_objective(const ChainArgs &a, int dtype, int vec, int loss, const float *w, double lambda,
                             double *partials, double *out, hipStream_t s)
 {
