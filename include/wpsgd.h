@@ -37,7 +37,8 @@ typedef enum {
     WPSGD_INVALID_ARG = -1,        /* NULL pointer, size out of range, bad enum, eta*lambda >= 1 ... */
     WPSGD_HIP_ERROR = -2,          /* a HIP call failed; see wpsgd_last_hip_error()                  */
     WPSGD_WORKSPACE_TOO_SMALL = -3,
-    WPSGD_UNSUPPORTED = -4         /* a forced plan that no kernel implements                        */
+    WPSGD_UNSUPPORTED = -4,        /* a forced plan that no kernel implements                        */
+    WPSGD_INCOMPLETE = -5          /* reported by wpsgd_chains_status: some chains could not finish  */
 } wpsgd_status;
 
 /* L(x, y, yhat) of Eq. 4, a convex function of yhat = w.x:
@@ -95,10 +96,17 @@ typedef struct wpsgd_plan {
                             threads, compute units permitting); 1: a chain is one workgroup; 2..8: that
                             many, which must be what some 256-thread shape needs to cover d.
                             The slices of a chain wait for each other, so all k*slices workgroups must
-                            be running at once: on a device that is busy with other kernels some may not
-                            be seated in time, and a slice that has waited in vain (some tens of
-                            milliseconds) ends and fills its columns of W with NaN.  Callers who share
-                            the device pass slices = 1.                                               */
+                            be running at once.  The library sees to it where it can: a sliced launch
+                            never has more workgroups than the device has compute units, and within one
+                            process sliced launches run one after the other whatever streams they are
+                            queued on.  What it cannot see (another process that keeps the device busy)
+                            can still seat some slices late; a slice that has waited slice_wait_us in
+                            vain ends, the chain's row of W is NaN, and wpsgd_chains_status reports
+                            WPSGD_INCOMPLETE.                                                          */
+    int slice_wait_us;   /* about how long a column slice waits for the others' sums before it gives up, in
+                            microseconds, at most 60 s (the kernel counts polls: it waits at least this long
+                            and at most about twice as long).  0: two seconds.  -1: not at all, so that every
+                            sliced chain gives up at its first exchange (a test of that path)          */
 } wpsgd_plan;
 
 /* ---- per-chain SGD (Algorithm 1, the loop over n = 1..t-T_i; Eq. 5 with Eq. 4) ----
@@ -137,6 +145,13 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
                           double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
                           const float *w_start, const int64_t *step_offsets, float *W,
                           void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream);
+
+/* Did every chain of the last wpsgd_run_chains, wpsgd_run_chains_from or wpsgd_run_spans call on
+ * this workspace (all spans of it) finish?  Waits for `stream`, on which that call was queued, and
+ * reads the status word the kernels keep at the start of the workspace.
+ * Returns WPSGD_OK, or WPSGD_INCOMPLETE if chains that were cut into column slices gave up waiting
+ * for each other (their rows of W, and whatever was computed from them, are NaN), or an error.   */
+int wpsgd_chains_status(const void *workspace, void *stream);
 
 /* ---- weights (Eq. 6; Eq. 8 for a chosen contraction rate r) ----
  *   a[i] = rate^{T_i} / sum_j rate^{T_j},  T_i = max_j n_steps[j] - n_steps[i],

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libwpsgd.so")
 HINGE, LOGISTIC = 0, 1
 SAMPLE_STREAM, SAMPLE_SHARDS = 0, 1
 F32, BF16 = 0, 1
-OK, INVALID_ARG, HIP_ERROR, WORKSPACE_TOO_SMALL, UNSUPPORTED = 0, -1, -2, -3, -4
+OK, INVALID_ARG, HIP_ERROR, WORKSPACE_TOO_SMALL, UNSUPPORTED, INCOMPLETE = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [
     "wpsgd_run_chains_workspace", "wpsgd_run_chains", "wpsgd_weights", "wpsgd_weights_rate",
@@ -29,6 +29,7 @@ EXPORTS = [
     "wpsgd_stream_rows", "wpsgd_objective_workspace", "wpsgd_objective",
     "wpsgd_run_chains_from", "wpsgd_shard_indices", "wpsgd_shard_indices_device",
     "wpsgd_run_spans_workspace", "wpsgd_run_spans", "wpsgd_span_condition", "wpsgd_objective_static",
+    "wpsgd_chains_status",
 ]
 
 
@@ -41,7 +42,8 @@ class _CMatrix(ctypes.Structure):
 class _CPlan(ctypes.Structure):
     _fields_ = [("threads", ctypes.c_int), ("block_steps", ctypes.c_int),
                 ("prefetch", ctypes.c_int), ("state_in_hbm", ctypes.c_int),
-                ("rows", ctypes.c_int), ("helpers", ctypes.c_int), ("slices", ctypes.c_int)]
+                ("rows", ctypes.c_int), ("helpers", ctypes.c_int), ("slices", ctypes.c_int),
+                ("slice_wait_us", ctypes.c_int)]
 
 
 class WpsgdError(RuntimeError):
@@ -71,6 +73,7 @@ def load():
     L.wpsgd_run_chains_workspace.restype = sz
     L.wpsgd_run_chains.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, sz, pp, vp]
     L.wpsgd_run_chains_from.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, ci, vp, vp, vp, vp, sz, pp, vp]
+    L.wpsgd_chains_status.argtypes = [vp, vp]
     L.wpsgd_run_spans_workspace.argtypes = [pm, ci, ci, pp]
     L.wpsgd_run_spans_workspace.restype = sz
     L.wpsgd_run_spans.argtypes = [pm, vp, ci, vp, i64, f64, f64, ci, u64, ci, vp, vp, vp, sz, pp, vp]
@@ -151,6 +154,7 @@ def _plan(plan):
     p.rows = int(plan.get("rows", 0))
     p.helpers = int(plan.get("helpers", 0))
     p.slices = int(plan.get("slices", 0))
+    p.slice_wait_us = int(plan.get("slice_wait_us", 0))
     return ctypes.byref(p)
 
 
@@ -213,6 +217,14 @@ def wpsgd_run_chains(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
     return W
 
 
+def wpsgd_chains_status(workspace: torch.Tensor, stream=None) -> int:
+    """OK, or INCOMPLETE when chains of the last call on this workspace gave up (waits for the stream)."""
+    rc = load().wpsgd_chains_status(workspace.data_ptr(), _stream(stream))
+    if rc not in (OK, INCOMPLETE):
+        raise WpsgdError(rc, "wpsgd_chains_status")
+    return rc
+
+
 def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, seed,
                           w_start: Optional[torch.Tensor] = None, step_offsets=None, sampling=0,
                           W: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
@@ -245,6 +257,11 @@ def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, s
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_run_chains_from")
     return W
+
+
+def wpsgd_run_spans_workspace(X: Matrix, k, loss, plan=None) -> int:
+    cm = X.c_struct()
+    return int(load().wpsgd_run_spans_workspace(ctypes.byref(cm), int(k), int(loss), _plan(plan)))
 
 
 def wpsgd_run_spans(X: Matrix, y: torch.Tensor, steps_per_span, n_spans, eta, lam, loss, seed,

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <numeric>
 #include <vector>
 
@@ -48,6 +49,8 @@ static bool dense_reg_shape(int dtype, int loss, int threads, int ept, int vec)
     return loss == WPSGD_HINGE ? dense_reg_shape_f32_loss0(threads, ept, vec)
                                : dense_reg_shape_f32_loss1(threads, ept, vec);
 }
+
+static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 static int check_matrix(const wpsgd_matrix *X)
 {
@@ -97,8 +100,9 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     p.loss = (int)loss;
     p.dtype = X->dense ? (int)X->dtype : WPSGD_F32;
     const size_t state_elem = (loss == WPSGD_HINGE) ? sizeof(double) : sizeof(float);
-    const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0, 0, 0, 0};
+    const wpsgd_plan f = force ? *force : wpsgd_plan{0, 0, 0, 0, 0, 0, 0, 0};
     if (f.threads < 0 || f.block_steps < 0 || f.prefetch < 0 || f.rows < 0 || f.rows > 3 || f.helpers < -1 || f.helpers > 3 || f.slices < 0 || f.slices > 8) return WPSGD_INVALID_ARG;
+    if (f.slice_wait_us < -1 || f.slice_wait_us > 60 * 1000 * 1000) return WPSGD_INVALID_ARG;
 
     if (!X->dense) {
         if (f.threads && f.threads != kWave && f.threads != 2 * kWave) return WPSGD_UNSUPPORTED;
@@ -220,7 +224,6 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     return WPSGD_OK;
 }
 
-static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 // shuffled row order of partition-and-shuffle sampling (always reserved: the workspace query does
 // not know which sampling a call will ask for)
@@ -231,16 +234,30 @@ static size_t state_elem_bytes(wpsgd_loss loss)
     return loss == WPSGD_HINGE ? sizeof(double) : sizeof(float);
 }
 
-// workspace header: chain order, then (in that order) step counts, stream offsets, three 32-bit
-// numbers per chain describing its share under partition-and-shuffle sampling, and a progress
-// counter per chain (zero at launch) that helper workgroups watch; last, the powers
-// (1-eta*lambda)^l and (1-eta*lambda)^-(l+1), l = 0..63, in fp64
+// Workspace header.  First a status block (word 0: bit 0 set by chains that could not finish, see
+// wpsgd_chains_status); then the chain order; then, in that order, step counts, stream offsets,
+// three 32-bit numbers per chain describing its share under partition-and-shuffle sampling, and a
+// progress counter per chain (zero at launch) that helper workgroups watch; last, the powers
+// (1-eta*lambda)^l and (1-eta*lambda)^-(l+1), l = 0..63, in fp64.  Every part is 256-byte aligned.
+constexpr size_t kStatusBytes = 256;
+constexpr int kSliceWaitDefaultUs = 2 * 1000 * 1000;      // two seconds
 constexpr size_t kPowTabBytes = 2 * 64 * sizeof(double);
-static size_t header_bytes(int k)
+struct HeaderLayout {
+    size_t order, steps, offsets, shard, progress, pow_tab, total;
+};
+static HeaderLayout header_layout(int k)
 {
-    return align256((size_t)k * sizeof(int32_t)) + 2 * align256((size_t)k * sizeof(int64_t)) +
-           align256((size_t)k * 3 * sizeof(uint32_t)) + align256(((size_t)k * 2 + 16) * sizeof(uint32_t)) + kPowTabBytes;
+    HeaderLayout h;
+    h.order = kStatusBytes;
+    h.steps = h.order + align256((size_t)k * sizeof(int32_t));
+    h.offsets = h.steps + align256((size_t)k * sizeof(int64_t));
+    h.shard = h.offsets + align256((size_t)k * sizeof(int64_t));
+    h.progress = h.shard + align256((size_t)k * 3 * sizeof(uint32_t));
+    h.pow_tab = h.progress + align256(((size_t)k * 2 + 16) * sizeof(uint32_t));
+    h.total = h.pow_tab + kPowTabBytes;
+    return h;
 }
+static size_t header_bytes(int k) { return header_layout(k).total; }
 
 // 32-bit words of the table the column slices of k chains exchange their sums through: per chain
 // 8 slices x 2 round parities x 32 words of records, then 8 words (the slices' XCD numbers)
@@ -390,10 +407,24 @@ int wpsgd_run_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t
                                  workspace, workspace_bytes, plan, stream);
 }
 
-int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
-                          double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
-                          const float *w_start, const int64_t *step_offsets, float *W,
-                          void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream)
+// Chains cut into column slices wait for each other's workgroups.  Two such launches seated half and
+// half on the device would each wait for workgroups that cannot start before the other launch's have
+// ended, so within this process they run one after the other: a launch first makes its stream wait
+// for the previous sliced launch on the device (on whatever stream that was queued).
+struct SlicedLaunchOrder {
+    static constexpr int kMaxDevices = 64;
+    std::mutex lock;
+    hipEvent_t last[kMaxDevices] = {};
+    bool queued[kMaxDevices] = {};
+};
+static SlicedLaunchOrder g_sliced;
+
+// keep_status: leave the status word as earlier launches on this workspace left it (later spans of
+// wpsgd_run_spans); otherwise it is cleared along with the header.
+static int run_chains_from(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
+                           double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
+                           const float *w_start, const int64_t *step_offsets, float *W,
+                           void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream, bool keep_status)
 {
     int rc = check_matrix(X);
     if (rc != WPSGD_OK) return rc;
@@ -416,7 +447,8 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     // table the column slices of a chain exchange their sums through
     const bool sliced = p.family == Family::DenseReg && p.slices > 1;
     const size_t behind = sliced ? slice_table_words(k) * sizeof(uint32_t) : (size_t)k * (size_t)X->d * p.state_bytes_per_elem;
-    const size_t need = header_bytes(k) + perm_bytes(X->m) + align256(behind);
+    const HeaderLayout h = header_layout(k);
+    const size_t need = h.total + perm_bytes(X->m) + align256(behind);
     if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
     if (workspace_bytes < need) return WPSGD_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -427,13 +459,11 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
                      [&](int32_t x, int32_t z) { return n_steps[x] > n_steps[z]; });
-    const size_t order_bytes = align256((size_t)k * sizeof(int32_t));
-    std::vector<char> header(header_bytes(k), 0);
-    std::memcpy(header.data(), order.data(), (size_t)k * sizeof(int32_t));
-    const size_t steps_bytes = align256((size_t)k * sizeof(int64_t));
-    int64_t *sorted_steps = reinterpret_cast<int64_t *>(header.data() + order_bytes);
-    int64_t *sorted_offsets = reinterpret_cast<int64_t *>(header.data() + order_bytes + steps_bytes);
-    uint32_t *shard = reinterpret_cast<uint32_t *>(header.data() + order_bytes + 2 * steps_bytes);
+    std::vector<char> header(h.total, 0);
+    std::memcpy(header.data() + h.order, order.data(), (size_t)k * sizeof(int32_t));
+    int64_t *sorted_steps = reinterpret_cast<int64_t *>(header.data() + h.steps);
+    int64_t *sorted_offsets = reinterpret_cast<int64_t *>(header.data() + h.offsets);
+    uint32_t *shard = reinterpret_cast<uint32_t *>(header.data() + h.shard);
     for (int b = 0; b < k; ++b) {
         sorted_steps[b] = n_steps[order[b]];
         sorted_offsets[b] = step_offsets ? step_offsets[order[b]] : 0;
@@ -446,7 +476,7 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
         }
     }
 
-    double *pow_tab = reinterpret_cast<double *>(header.data() + header.size() - kPowTabBytes);
+    double *pow_tab = reinterpret_cast<double *>(header.data() + h.pow_tab);
     {
         const double rho = 1.0 - eta * lambda, inv_rho = 1.0 / rho;
         double up = 1.0, down = inv_rho;
@@ -458,12 +488,10 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
         }
     }
     char *ws = static_cast<char *>(workspace);
-    int32_t *order_dev = reinterpret_cast<int32_t *>(ws);
-    int64_t *steps_dev = reinterpret_cast<int64_t *>(ws + order_bytes);
-    int64_t *offsets_dev = reinterpret_cast<int64_t *>(ws + order_bytes + steps_bytes);
-    uint32_t *perm_dev = reinterpret_cast<uint32_t *>(ws + header_bytes(k));
-    void *state_dev = ws + header_bytes(k) + perm_bytes(X->m);
-    rc = upload(ws, header.data(), header.size(), s);
+    uint32_t *perm_dev = reinterpret_cast<uint32_t *>(ws + h.total);
+    void *state_dev = ws + h.total + perm_bytes(X->m);
+    const size_t from = keep_status ? kStatusBytes : 0;           // (the status block is zero in `header`)
+    rc = upload(ws + from, header.data() + from, header.size() - from, s);
     if (rc != WPSGD_OK) return rc;
 
     ChainArgs a{};
@@ -476,15 +504,21 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
     a.m = X->m;
     a.d = X->d;
     a.k = k;
-    a.order = order_dev;
-    a.nsteps = steps_dev;
-    a.step0 = offsets_dev;
+    a.status = reinterpret_cast<uint32_t *>(ws);
+    a.order = reinterpret_cast<const int32_t *>(ws + h.order);
+    a.nsteps = reinterpret_cast<const int64_t *>(ws + h.steps);
+    a.step0 = reinterpret_cast<const int64_t *>(ws + h.offsets);
     a.w_start = w_start;
-    a.pow_tab = reinterpret_cast<const double *>(ws + header_bytes(k) - kPowTabBytes);
-    a.progress = reinterpret_cast<uint32_t *>(ws + order_bytes + 2 * steps_bytes + align256((size_t)k * 3 * sizeof(uint32_t)));
+    a.pow_tab = reinterpret_cast<const double *>(ws + h.pow_tab);
+    a.progress = reinterpret_cast<uint32_t *>(ws + h.progress);
     a.helpers = helpers_per_chain(p, X, k, plan) * k;
     a.slices = sliced ? p.slices : 1;
     a.xchg = state_dev;
+    // how long a slice waits for the others before it gives up, as a number of polls: a poll takes 600 to
+    // 1200 cycles of a 2.4 GHz clock, so four polls per microsecond are at least the time asked for and
+    // at most twice that; 0: no poll at all (the plan's test hook)
+    const int wait_us = plan ? plan->slice_wait_us : 0;
+    a.slice_max_polls = wait_us < 0 ? 0u : (uint32_t)std::min<int64_t>((int64_t)(wait_us > 0 ? wait_us : kSliceWaitDefaultUs) * 4, INT32_MAX);
     if (a.slices > 1) {
         hipError_t ze = launch_zero_words(static_cast<uint32_t *>(state_dev), slice_table_words(k), s);
         if (ze != hipSuccess) return hip_fail(ze);
@@ -498,19 +532,60 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
         hipError_t pe = launch_permute_rows(a.seed_lo, a.seed_hi, (uint32_t)X->m, perm_dev, s);
         if (pe != hipSuccess) return hip_fail(pe);
         a.perm = perm_dev;
-        a.shard = reinterpret_cast<const uint32_t *>(ws + order_bytes + 2 * steps_bytes);
+        a.shard = reinterpret_cast<const uint32_t *>(ws + h.shard);
     }
     a.W = W;
     a.state = state_dev;
 
     hipError_t e;
-    switch (p.family) {
-    case Family::DenseReg: e = dense_reg_dispatch(p, &a, s); break;
-    case Family::DenseMem: e = launch_dense_mem(p, a, s); break;
-    default: e = launch_csr(p, a, s); break;
+    if (a.slices > 1) {
+        int dev = 0;
+        e = hipGetDevice(&dev);
+        if (e != hipSuccess) return hip_fail(e);
+        if (dev < 0 || dev >= SlicedLaunchOrder::kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+        std::lock_guard<std::mutex> guard(g_sliced.lock);
+        if (!g_sliced.last[dev]) {
+            e = hipEventCreateWithFlags(&g_sliced.last[dev], hipEventDisableTiming);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        if (g_sliced.queued[dev]) {
+            e = hipStreamWaitEvent(s, g_sliced.last[dev], 0);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        e = dense_reg_dispatch(p, &a, s);
+        if (e == hipSuccess) {
+            e = hipEventRecord(g_sliced.last[dev], s);
+            g_sliced.queued[dev] = e == hipSuccess;
+        }
+    } else {
+        switch (p.family) {
+        case Family::DenseReg: e = dense_reg_dispatch(p, &a, s); break;
+        case Family::DenseMem: e = launch_dense_mem(p, a, s); break;
+        default: e = launch_csr(p, a, s); break;
+        }
     }
     if (e == hipErrorInvalidValue) return WPSGD_UNSUPPORTED;
     return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
+int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_steps,
+                          double eta, double lambda, wpsgd_loss loss, uint64_t seed, wpsgd_sampling sampling,
+                          const float *w_start, const int64_t *step_offsets, float *W,
+                          void *workspace, size_t workspace_bytes, const wpsgd_plan *plan, void *stream)
+{
+    return run_chains_from(X, y, k, n_steps, eta, lambda, loss, seed, sampling, w_start, step_offsets, W, workspace,
+                           workspace_bytes, plan, stream, false);
+}
+
+int wpsgd_chains_status(const void *workspace, void *stream)
+{
+    if (!workspace) return WPSGD_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t word = 0;
+    hipError_t e = hipMemcpyAsync(&word, workspace, sizeof(word), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e);
+    return (word & 1u) ? WPSGD_INCOMPLETE : WPSGD_OK;
 }
 
 int wpsgd_weights_rate(int k, const int64_t *n_steps, double rate, double *a)
@@ -588,7 +663,7 @@ size_t wpsgd_run_spans_workspace(const wpsgd_matrix *X, int k, wpsgd_loss loss, 
 {
     const size_t chains = wpsgd_run_chains_workspace(X, k, loss, plan);
     if (chains == 0) return 0;
-    return align256((size_t)k * (size_t)X->d * sizeof(float)) + chains + wpsgd_combine_workspace(k, X->d);
+    return chains + align256((size_t)k * (size_t)X->d * sizeof(float)) + wpsgd_combine_workspace(k, X->d);
 }
 
 int wpsgd_run_spans(const wpsgd_matrix *X, const float *y, int k, const int64_t *steps_per_span, int64_t n_spans,
@@ -605,27 +680,28 @@ int wpsgd_run_spans(const wpsgd_matrix *X, const float *y, int k, const int64_t 
     for (int i = 0; i < k; ++i) span = std::max(span, steps_per_span[i]);
     if (span < 1 || span > ((int64_t)1 << 62) / n_spans) return WPSGD_INVALID_ARG;
     if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
-    const size_t models = align256((size_t)k * (size_t)X->d * sizeof(float));
+    // the chains' workspace comes first, so that its status word is the first word of this one too
     const size_t chains = wpsgd_run_chains_workspace(X, k, loss, plan);
+    const size_t models = align256((size_t)k * (size_t)X->d * sizeof(float));
     const size_t average = wpsgd_combine_workspace(k, X->d);
     if (chains == 0) return WPSGD_UNSUPPORTED;
-    if (workspace_bytes < models + chains + average) return WPSGD_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < chains + models + average) return WPSGD_WORKSPACE_TOO_SMALL;
     char *ws = static_cast<char *>(workspace);
-    float *W = reinterpret_cast<float *>(ws);
+    float *W = reinterpret_cast<float *>(ws + chains);
     std::vector<double> a(k);
     rc = wpsgd_weights(k, steps_per_span, eta, lambda, a.data());
     if (rc != WPSGD_OK) return rc;
     std::vector<int64_t> first(k);
     for (int64_t sp = 0; sp < n_spans; ++sp) {
         for (int i = 0; i < k; ++i) first[i] = sp * steps_per_span[i];
-        rc = wpsgd_run_chains_from(X, y, k, steps_per_span, eta, lambda, loss, seed, sampling, sp == 0 ? w_start : w_out,
-                                   first.data(), W, ws + models, chains, plan, stream);
+        rc = run_chains_from(X, y, k, steps_per_span, eta, lambda, loss, seed, sampling, sp == 0 ? w_start : w_out,
+                             first.data(), W, ws, chains, plan, stream, sp > 0);
         if (rc != WPSGD_OK) return rc;
         if (sp == 0) {          // (this call also carries the weights to the device; they stay there for the spans to come)
-            rc = wpsgd_combine(W, a.data(), k, X->d, w_out, ws + models + chains, average, stream);
+            rc = wpsgd_combine(W, a.data(), k, X->d, w_out, ws + chains + models, average, stream);
             if (rc != WPSGD_OK) return rc;
         } else {
-            hipError_t e = launch_combine(W, reinterpret_cast<const double *>(ws + models + chains), k, X->d, w_out,
+            hipError_t e = launch_combine(W, reinterpret_cast<const double *>(ws + chains + models), k, X->d, w_out,
                                           static_cast<hipStream_t>(stream));
             if (e != hipSuccess) return hip_fail(e);
         }
@@ -778,6 +854,7 @@ const char *wpsgd_strerror(int status)
     case WPSGD_HIP_ERROR: return "HIP call failed (see wpsgd_last_hip_error)";
     case WPSGD_WORKSPACE_TOO_SMALL: return "workspace too small";
     case WPSGD_UNSUPPORTED: return "no kernel implements the forced plan";
+    case WPSGD_INCOMPLETE: return "chains cut into column slices gave up waiting for each other; their rows of W are NaN";
     default: return "unknown status";
     }
 }

@@ -68,6 +68,15 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
     __shared__ TV red[2][NR][NW];
     // Labels of a whole window, gathered straight into LDS one window ahead (per wave, two windows)
     __shared__ float ylab[NW][2][kWave];
+    // Sliced chains: the workgroup's verdict at the end of the chain (did a wave give up waiting for
+    // the other slices?), reached by one vote behind the loop.
+    __shared__ uint32_t gave_up_word;
+    typedef __attribute__((address_space(3))) volatile uint32_t *lds_flag_ptr;      // (LDS-typed: no flat accesses)
+    const lds_flag_ptr gave_up = (lds_flag_ptr)&gave_up_word;
+    if constexpr (SLICED) {
+        if (threadIdx.x == 0) *gave_up = 0u;
+        __syncthreads();
+    }
 
     if constexpr (!SLICED) {
         if ((int)blockIdx.x >= a.k) {              // a helper workgroup: see run_ahead_of_chain
@@ -222,6 +231,10 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         request_labels(1, rows_b);
 
         uint32_t round_no = 0;              // rounds done, as the slices of a chain count them
+        // who publishes a slice's sums; nobody when slices are told not to wait at all (then no record
+        // ever shows up and every wave of every slice gives up at its first exchange)
+        const bool publisher = tid == 0 && a.slice_max_polls != 0;
+        uint32_t max_polls = a.slice_max_polls;        // how long an exchange may wait for the other slices
         bool near_slices = false;
         if constexpr (SLICED) near_slices = slices_share_an_xcd(a, cb, slice, tid == 0);
         int parity = 0;
@@ -331,9 +344,17 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                         w[r] = __float_as_uint((float)tot[r]);
                     }
                 }
-                const bool met = near_slices ? slices_all_reduce<sizeof(TV) == 8, NR, true>(a, cb, slice, tid == 0, round_no, w)
-                                             : slices_all_reduce<sizeof(TV) == 8, NR, false>(a, cb, slice, tid == 0, round_no, w);
-                if (!met) lost = true;
+                const bool met = near_slices ? slices_all_reduce<sizeof(TV) == 8, NR, true>(a, cb, slice, publisher, round_no, max_polls, w)
+                                             : slices_all_reduce<sizeof(TV) == 8, NR, false>(a, cb, slice, publisher, round_no, max_polls, w);
+                if (__builtin_expect(!met, 0)) {
+                    // The wait for the other slices ran out.  The wave tells the host, waits no more in the
+                    // rounds left of its group, and leaves the chain at the group's end (see there).
+                    lost = true;
+                    max_polls = 0;
+#pragma unroll
+                    for (int q = 0; q < kSliceMaxWords; ++q) w[q] = 0x7ff80000u;      // NaN as a float, and as either half of a double
+                    if (lane == kWave - 1) __hip_atomic_fetch_or(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
                 if constexpr (P > 1) issue_rows(u_prev, next_rows, 0, kFirstHalf);
 #pragma unroll
                 for (int r = 0; r < NR; ++r) {
@@ -360,7 +381,11 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
                     }
                 if constexpr (LOSS == kLossHinge) {
                     // -eta*g/s_next, g = -y or 0
-                    if constexpr (NW > 1) {
+                    if constexpr (SLICED) {
+                        // (dot - dot is 0 for every number and NaN for NaN: a chain whose slices lost each
+                        // other must not turn NaN sums into steps not taken)
+                        c[b] = (zy[b] * dot < 1.0) ? cy[b] : dot - dot;
+                    } else if constexpr (NW > 1) {
                         c[b] = (zy[b] * dot < 1.0) ? cy[b] : 0.0;
                     } else {
                         c[b] = lane63_below_one(zy[b], dot) ? cy[b] : 0.0;
@@ -453,6 +478,25 @@ __global__ __launch_bounds__(NT) void chain_dense_reg_kernel(ChainArgs a)
         __builtin_amdgcn_s_waitcnt(0x0F70);      // no label load may still be on its way to LDS when the wave ends
         if constexpr (!SLICED) {
             if (a.helpers > 0 && tid == 0) a.progress[cb] = kChainDone;
+        }
+        if constexpr (SLICED) {
+            // A wave that gave up turns its partial sums into NaN for good before it goes (nobody else
+            // writes those words): from the next round on every sum of this slice is NaN, so is the
+            // record it publishes, and so are the totals, the steps and the model of every slice of
+            // the chain.  The failure travels with the data; a round that goes well carries no check
+            // for it.  Then one verdict for the workgroup: if any of its waves gave up, all of its
+            // columns are NaN, also when that happened in the chain's last rounds.  (A wave that left
+            // the loop early may meet the others at this barrier while they are still at a round's.)
+            if (lost && lane == kWave - 1) {
+#pragma unroll
+                for (int r = 0; r < NR; ++r) {
+                    red[0][r][wave] = (TV)__builtin_nanf("");
+                    red[1][r][wave] = (TV)__builtin_nanf("");
+                }
+                *gave_up = 1u;
+            }
+            __syncthreads();
+            if (*gave_up != 0u) lost = true;
         }
         // scale at the chain's end: s_w covers the steps before the last window
         const int64_t last_w = (n - 1) / kWave;

@@ -73,8 +73,8 @@ __device__ inline uint32_t xcd_of_this_wave()
 // round's record and half of another's.  The same parity's records are written again only two
 // rounds later, after their writer has read every slice's record of the round in between, which
 // those slices published after reading this one: nobody still reads a record when it is
-// overwritten.  Every wait has a budget; a slice that loses the others fills its part of the
-// result with NaN and ends.
+// overwritten.  Every wait has a budget; a slice that loses the others says so in the workspace's
+// status word, fills its part of the result with NaN and ends.
 //
 // The accepted sums sit in lanes 0..7 (zero beyond the last slice) and are added by three
 // exchange levels among those lanes: one fixed tree, the same in every wave of every slice, so all
@@ -217,10 +217,10 @@ __device__ inline double from_other_lane(double v)
 
 // Adds the slices' sums for this round, in one fixed tree.  w holds NVAL values of this slice (fp32:
 // one word each; fp64: two), identical in every wave of the slice; lane 0 of wave 0 publishes them.
-// Returns false if the other slices did not show up.
+// Returns false if the other slices did not show up within max_polls polls.
 template <bool IS_F64, int NVAL, bool NEAR>
 __device__ inline bool slices_all_reduce(const ChainArgs &a, int chain_block, int slice, bool publisher, uint32_t round,
-                                         uint32_t (&w)[kSliceMaxWords])
+                                         uint32_t max_polls, uint32_t (&w)[kSliceMaxWords])
 {
     constexpr int NWORDS = IS_F64 ? 2 * NVAL : NVAL;
     static_assert(NWORDS <= kSliceMaxWords, "a slot holds twelve words");
@@ -237,8 +237,12 @@ __device__ inline bool slices_all_reduce(const ChainArgs &a, int chain_block, in
     const int src = lane < a.slices ? lane : 0;                   // lanes beyond the slices repeat slice 0
     const uint32_t *slot = slice_slot(a, chain_block, src, parity);
     uint32_t got[kSliceMaxWords];
+    // The first poll usually finds every record.  The wait is bounded by a number of polls the host has
+    // worked out from the time it allows (a poll takes 600 to 1200 cycles).  (A clock read in this loop,
+    // or a second copy of the poll behind the first, cost 3 % of a pass although neither is ever reached
+    // when all goes well: the loop keeps the shape it was tuned in.)
     bool all = false;
-    for (int tries = 0; tries < (1 << 17) && !all; ++tries)
+    for (uint32_t tries = 0; tries < max_polls && !all; ++tries)
         all = __builtin_amdgcn_ballot_w64(slice_read<NWORDS>(slot, stamp, got)) == ~0ull;
     if (!all) return false;
     if constexpr (IS_F64) {

@@ -45,6 +45,9 @@ struct ChainArgs {
     // xchg is the table the slices add their partial sums through (zero at launch), else unused.
     int slices;               // 1: a chain is one workgroup
     void *xchg;               // DEVICE, k * 8 * 2 slots of 128 bytes, then k * 8 words (the slices' XCD numbers)
+    uint32_t slice_max_polls; // how often a slice polls for the others' sums before it gives up (a poll takes
+                              // 600 to 1200 cycles); 0: it does not poll at all
+    uint32_t *status;         // DEVICE, first word of the workspace: bit 0 is set by a slice that gave up
     // outputs / scratch
     float *W;                 // k x d
     void *state;              // k x d model vectors in HBM (state_in_hbm plans), else unused

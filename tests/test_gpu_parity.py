@@ -215,6 +215,73 @@ def test_dense_chains_cut_into_column_slices(d, bf16, loss, plan):
     assert torch.equal(W, gpu_chains(w, plan=plan, X=Xg))            # same inputs, same bits
 
 
+def _wide_case(seed, k=32, d=65536, m=200, n_hi=260):
+    rng = np.random.default_rng(seed)
+    Xf = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    bits = wl.f32_to_bf16_bits(Xf)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = rng.integers(40, n_hi, size=k).astype(np.int64)
+    return wl.Workload("wide_pair", wl.LOGISTIC, 0.5, 1e-3, seed, n, y, m, d, dense=bits)
+
+
+def test_two_sliced_launches_on_two_streams_at_once():
+    """Two default launches of few wide chains (each cut into as many column slices as the device has
+    compute units for) queued on two streams at the same time: the slices of a chain wait for each
+    other, so the two launches must not end up half seated each.  Both match the oracle."""
+    wa, wb = _wide_case(101), _wide_case(202)
+    Xa, Xb = api.matrix_from_workload(wa), api.matrix_from_workload(wb)
+    assert "slices=8" in api.wpsgd_describe_plan(Xa, wa.k, wa.loss)
+    ya, yb = torch.from_numpy(wa.y).cuda(), torch.from_numpy(wb.y).cuda()
+    ws_a = torch.empty(api.wpsgd_run_chains_workspace(Xa, wa.k, wa.loss), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(api.wpsgd_run_chains_workspace(Xb, wb.k, wb.loss), dtype=torch.uint8, device="cuda")
+    Wa = torch.empty((wa.k, wa.d), dtype=torch.float32, device="cuda")
+    Wb = torch.empty((wb.k, wb.d), dtype=torch.float32, device="cuda")
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(3):                 # several pairs back to back, so that launches do meet on the device
+        api.wpsgd_run_chains(Xa, ya, wa.n_steps, wa.eta, wa.lam, wa.loss, wa.seed, W=Wa, workspace=ws_a, stream=sa)
+        api.wpsgd_run_chains(Xb, yb, wb.n_steps, wb.eta, wb.lam, wb.loss, wb.seed, W=Wb, workspace=ws_b, stream=sb)
+    assert api.wpsgd_chains_status(ws_a, stream=sa) == api.OK
+    assert api.wpsgd_chains_status(ws_b, stream=sb) == api.OK
+    torch.cuda.synchronize()
+    check_against_oracle(wa, Wa, label="sliced pair, first stream")
+    check_against_oracle(wb, Wb, label="sliced pair, second stream")
+
+
+@pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
+def test_slices_that_give_up_say_so(loss):
+    """The give-up path of sliced chains, forced from the host: with no time to wait, every slice
+    loses the others at its first exchange.  Every kernel still ends by itself; the rows of the chains
+    that took steps are NaN through and through, idle chains are untouched, the status word reports
+    it, and the next ordinary call on the same workspace is clean again."""
+    rng = np.random.default_rng(31 + loss)
+    m, d, k = 120, 8192, 5
+    Xf = (rng.standard_normal((m, d)) / math.sqrt(d)).astype(np.float32)
+    y = np.where(rng.random(m) < 0.5, 1.0, -1.0).astype(np.float32)
+    n = np.array([90, 0, 33, 64, 1], dtype=np.int64)
+    w = wl.Workload("gave_up", loss, 0.5, 1e-3, 3, n, y, m, d, dense=Xf)
+    X = api.matrix_from_workload(w)
+    yg = torch.from_numpy(w.y).cuda()
+    ws = torch.empty(api.wpsgd_run_chains_workspace(X, k, loss, {"slices": 4}), dtype=torch.uint8, device="cuda")
+    W = api.wpsgd_run_chains(X, yg, n, w.eta, w.lam, loss, w.seed, workspace=ws, plan={"slices": 4, "slice_wait_us": -1})
+    assert api.wpsgd_chains_status(ws) == api.INCOMPLETE
+    Wh = W.cpu().numpy()
+    for i in range(k):
+        assert np.isnan(Wh[i]).all() if n[i] > 0 else (Wh[i] == 0).all(), f"chain {i}"
+    W = api.wpsgd_run_chains(X, yg, n, w.eta, w.lam, loss, w.seed, workspace=ws, plan={"slices": 4})
+    assert api.wpsgd_chains_status(ws) == api.OK
+    check_against_oracle(w, W, label="after a give-up")
+    # periodic averaging keeps the verdict of every span
+    spans_ws = torch.empty(api.wpsgd_run_spans_workspace(X, k, loss, {"slices": 4}), dtype=torch.uint8, device="cuda")
+    api.wpsgd_run_spans(X, yg, np.array([20, 10, 5, 20, 0]), 3, w.eta, w.lam, loss, w.seed, workspace=spans_ws,
+                        plan={"slices": 4})
+    assert api.wpsgd_chains_status(spans_ws) == api.OK
+    v = api.wpsgd_run_spans(X, yg, np.array([20, 10, 5, 20, 0]), 3, w.eta, w.lam, loss, w.seed, workspace=spans_ws,
+                            plan={"slices": 4, "slice_wait_us": -1})
+    assert api.wpsgd_chains_status(spans_ws) == api.INCOMPLETE
+    assert torch.isnan(v).all()
+
+
 BF16_PLANS = [(64, None), (256, None), (512, None), (520, None), (2048, {"block_steps": 4}), (4096, None),
               (8192, {"block_steps": 1}), (16384, None), (30000, None), (65536, None),
               (65536, {"state_in_hbm": 1}), (4100, {"state_in_hbm": 1}), (40000, None), (33000, None),

@@ -99,6 +99,7 @@ def test_argument_errors_are_reported_not_crashed():
             bad()
         assert err.value.status == api.INVALID_ARG
     assert api.load().wpsgd_strerror(api.UNSUPPORTED).decode().startswith("no kernel")
+    assert "gave up" in api.load().wpsgd_strerror(api.INCOMPLETE).decode()
 
 
 class _FakeMatrix(api.Matrix):
@@ -184,15 +185,15 @@ def test_planner_shapes_cover_the_row_for_any_size():
 
 
 def test_workspace_sizes():
-    # chain order + step counts + stream offsets + share descriptions + progress counters (256-byte slots)
-    # + power table (1 KiB) + shuffled row order (4 bytes a row) + room for the model vectors in HBM
-    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 2304 + 4096 * 4 + 4 * 64 * 8
+    # status block + chain order + step counts + stream offsets + share descriptions + progress counters
+    # (256-byte slots) + power table (1 KiB) + shuffled row order (4 bytes a row) + room for the model vectors in HBM
+    assert api.wpsgd_run_chains_workspace(_FakeMatrix(4096, 64), 4, api.HINGE) == 2560 + 4096 * 4 + 4 * 64 * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.HINGE)
     assert ws >= 128 * (1 << 20) * 8
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.LOGISTIC)
-    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 2048 + 1024
+    assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 2048 + 1024 + 256
     assert api.wpsgd_combine_workspace(64, 4096) == 512
-    # spans: the chains' models, then what the chains and the average need
+    # spans: what the chains need, then the chains' models, then what the average needs
     fm = _FakeMatrix(4096, 64)
-    assert api.load().wpsgd_run_spans_workspace(ctypes.byref(fm.c_struct()), 4, api.HINGE, None) == \
-        1024 + api.wpsgd_run_chains_workspace(fm, 4, api.HINGE) + 256
+    assert api.wpsgd_run_spans_workspace(fm, 4, api.HINGE) == \
+        api.wpsgd_run_chains_workspace(fm, 4, api.HINGE) + 1024 + 256
