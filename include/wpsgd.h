@@ -73,12 +73,12 @@ typedef struct wpsgd_matrix {
 /* Optional kernel plan for wpsgd_run_chains; zero in a field means "choose for me".
  * Used by the tests and the tuner to reach every kernel variant at any size.      */
 typedef struct wpsgd_plan {
-    int threads;         /* workgroup size of a chain: 64, 256, 512 or 1024 (dense); 64 or 128 (CSR)    */
+    int threads;         /* workgroup size of a chain: 64, 256, 512 or 1024 (dense); 64 or 192 (CSR)    */
     int block_steps;     /* dense: SGD steps folded into one reduction round: 1, 2, 4 or 8              */
     int prefetch;        /* dense: rounds of sample rows kept in flight ahead of the one being consumed.
                             CSR: selects the kernel - 1 plain gather/scatter; 4 one wave per chain, hot
-                            columns in LDS, cold model values fetched 4 steps ahead; 8 the same with a
-                            second wave per chain that prepares the rows (the default)                  */
+                            columns in LDS, cold model values fetched 4 steps ahead; 8 the same with two
+                            more waves per chain that prepare the rows (the default)                  */
     int state_in_hbm;    /* 1: keep the model vector in the workspace (HBM) instead of registers        */
     int rows;            /* where a dense row waits between its dot product and its update:
                             1 registers, requested `prefetch` rounds ahead; 2 registers, with the next

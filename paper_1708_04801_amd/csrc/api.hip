@@ -105,13 +105,13 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
     if (f.slice_wait_us < -1 || f.slice_wait_us > 60 * 1000 * 1000) return WPSGD_INVALID_ARG;
 
     if (!X->dense) {
-        if (f.threads && f.threads != kWave && f.threads != 2 * kWave) return WPSGD_UNSUPPORTED;
+        if (f.threads && f.threads != kWave && f.threads != 3 * kWave) return WPSGD_UNSUPPORTED;
         if (f.block_steps > 1 || (f.prefetch > 1 && f.prefetch != 4 && f.prefetch != 8) || f.rows || f.slices > 1) return WPSGD_UNSUPPORTED;
         p.family = Family::Csr;
         p.threads = kWave;
         p.vec = 1;
         p.block_steps = 1;
-        // The LDS-cached kernels (prefetch 4: one wave per chain, 8: two) never fold their lazy scale
+        // The LDS-cached kernels (prefetch 4: one wave per chain, 8: three) never fold their lazy scale
         // back into the vector, so they need (1-eta*lambda)^steps to stay well inside fp32 range.
         // They park unused lanes on scratch columns at the start of the vector, and the two-wave
         // kernel addresses the vector with 32-bit byte offsets.
@@ -121,7 +121,7 @@ static int resolve_plan(const wpsgd_matrix *X, int k, wpsgd_loss loss, const wps
         if (f.prefetch == 4 && !cached_ok) return WPSGD_UNSUPPORTED;
         if (f.prefetch == 8 && !pair_ok) return WPSGD_UNSUPPORTED;
         p.prefetch = f.prefetch ? f.prefetch : (pair_ok ? 8 : (cached_ok ? 4 : 1));
-        if (p.prefetch == 8) p.threads = 2 * kWave;
+        if (p.prefetch == 8) p.threads = 3 * kWave;
         p.state_bytes_per_elem = state_elem;
         *out = p;
         return WPSGD_OK;

@@ -9,8 +9,9 @@
 //   scout   walks the chain's sample stream ahead of the worker.  For every step it fetches the
 //           row's entries and writes one 16-byte record per entry into an LDS ring: the value,
 //           the LDS address of the model element (or of a scratch slot), the offset of the model
-//           element in the HBM-resident part of the vector (or of a scratch element), and the
-//           two stamp slots of the column.  It also writes the per-step scalars of the recursion.
+//           element in the HBM-resident part of the vector (or an offset past its end, which the
+//           hardware turns into no access at all), and whether it is one.  It also writes the
+//           per-step scalars of the recursion and whether the step must re-read its values.
 //   worker  runs the recursion of Eq. 5 (w = s*v, the shrink carried by the scalar s) from the
 //           records: all its loads, stores and LDS accesses are unconditional and their
 //           addresses come ready-made.
@@ -21,17 +22,20 @@
 // the one section the worker is not reading.  Both waves execute the same number of barriers.
 //
 // Model values: columns below kPHead live in LDS; the others stay in HBM and are requested kTQ
-// steps ahead.  A value fetched early is stale if a step in between wrote the same column; every
-// write to an HBM-resident column leaves the step number in two LDS stamp tables (two different
-// hashes of the column), and a step that finds recent numbers in both for one of its columns
-// drains the memory queue and reads its values again.  A write always leaves both stamps, so a
-// conflict is never missed; two unrelated aliases at once cost a needless re-read.
+// steps ahead.  A value fetched early is stale if a step in between wrote the same column.  Whether
+// that can have happened depends on the rows alone, not on the model, so the scout decides it: it
+// keeps two LDS stamp tables (two different hashes of the column) with the step number of the last
+// write to each slot, and a step that finds recent numbers in both slots of one of its columns is
+// marked; the worker drains the memory queue and reads that step's values again.  A write always
+// leaves both stamps, so a conflict is never missed; two unrelated aliases at once cost a needless
+// re-read.  The worker carries no stamp traffic at all.
 //
 // Which writes can an early fetch miss?  Memory operations of one wave complete in issue order.
 // The values for step t+kTQ are requested at the end of step t, after step t has waited for its
 // own values, which were requested at the end of step t-kTQ, after that step's stores.  So all
 // stores of steps <= t-kTQ are complete by then, and the fetch for step t+kTQ can only miss the
 // writes of steps t-kTQ+1 .. t+kTQ-1: the 2*kTQ-1 steps before the one that uses it.
+#include <algorithm>
 #include <type_traits>
 
 #include "device_utils.h"
@@ -51,6 +55,7 @@ constexpr int kLead = 16;          // scout: entries are requested this many ste
 constexpr int kTQ = 4;             // worker: HBM-resident model values are requested this many steps ahead
 constexpr int kChunks = 2;         // entries of a row that go through records: kChunks * 64
 constexpr int kSlots = kChunks * kWave;
+constexpr int kPairThreads = 3 * kWave;     // the worker and two scouts
 constexpr uint32_t kRecordBytes = kSlots * 16;              // the records of one step ...
 constexpr uint32_t kStepBytes = kRecordBytes + 32;          // ... followed by its scalars (StepScalars, StepRow)
 constexpr uint32_t kSectionBytes = kG * kStepBytes;
@@ -155,7 +160,7 @@ __device__ inline uint32_t stamp_slot_a(uint32_t col) { return col & (kPStamps -
 __device__ inline uint32_t stamp_slot_b(uint32_t col) { return (col + (col >> 13) * 2731u) & (kPStamps - 1); }
 
 template <int LOSS>
-__global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
+__global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs a)
 {
     using TV = typename StateType<LOSS>::type;
     using L = Lds<TV>;
@@ -169,35 +174,28 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
     const int64_t n = a.nsteps[blockIdx.x];
     const int64_t d = a.d;
     TV *v = static_cast<TV *>(a.state) + (int64_t)chain * d;
-    float *out = a.W + (int64_t)chain * d;
     const int64_t nnz = a.row_ptr[a.m];
 
     const int64_t step0 = a.step0[blockIdx.x];
-    if (nnz == 0) {                     // no entries at all: every step only shrinks the start vector
-        double s_all = 1.0, pw = a.rho;
-        for (int64_t e = n; e > 0; e >>= 1) {
-            if (e & 1) s_all *= pw;
-            pw *= pw;
-        }
-        for (int64_t c = tid; c < d; c += 2 * kWave) out[c] = a.w_start ? (float)(s_all * (double)a.w_start[c]) : 0.0f;
-        return;
-    }
-    if (n == 0) {                       // no steps: the chain returns its start vector
-        for (int64_t c = tid; c < d; c += 2 * kWave) out[c] = a.w_start ? a.w_start[c] : 0.0f;
-        return;
-    }
+    // The vector in the workspace holds the chain's start vector on entry (csr_state_start_kernel)
+    // and is scaled into W after the launch (csr_state_finish_kernel): the chain itself touches
+    // only what its rows touch.  A chain without steps, or a matrix without entries (every step
+    // then only shrinks the vector), has nothing to do here.
+    if (nnz == 0 || n == 0) return;
     TV *head = reinterpret_cast<TV *>(lds + L::head);
-    for (int c = tid; c < kPHead + kSlots; c += 2 * kWave)                             // values and scratch slots
+    for (int c = tid; c < kPHead + kSlots; c += kPairThreads)                             // values and scratch slots
         head[c] = (a.w_start && c < kPHead && c < d) ? (TV)a.w_start[c] : (TV)0;
-    for (int c = tid; c < 2 * (kPStamps + kSlots); c += 2 * kWave) reinterpret_cast<uint16_t *>(lds + L::stamp_a)[c] = 0;
-    for (int64_t c = kPHead + tid; c < d; c += 2 * kWave) v[c] = a.w_start ? (TV)a.w_start[c] : (TV)0;
+    for (int c = tid; c < 2 * (kPStamps + kSlots); c += kPairThreads) reinterpret_cast<uint16_t *>(lds + L::stamp_a)[c] = 0;
     __syncthreads();
 
     const int64_t ngroups = (n + kG - 1) / kG;       // the worker runs groups 0..ngroups-1, the scout writes 0..ngroups
     const double rho = a.rho;
 
-    if (wave == 1) {
-        // ------------------------------------------------------------------------- scout
+    if (wave != 0) {
+        // ------------------------------------------------------------------------- scouts
+        // Wave 1 writes the records and the step scalars; wave 2 keeps the stamps and marks the steps
+        // that must re-read their values.  Both walk the sample stream the same way, kLead steps ahead
+        // of what they write, and both write into the section the worker is not reading.
         const uint32_t seed_lo = a.seed_lo, seed_hi = a.seed_hi, m32 = (uint32_t)a.m;
         const double inv_rho = 1.0 / rho;
         double rho_pow = 1.0, inv_rho_pow1 = inv_rho, rho64 = rho, inv_rho64 = inv_rho;
@@ -227,95 +225,137 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
         load_window(1, lo_b, len_b, y_b);
         StepScalars<TV> sc_tab;          // per lane: the scalars of step (window start + lane)
 
-        uint32_t er_col[kLead][kChunks], er_val[kLead][kChunks];
-        // entries of a row into ring slot `slot`; lanes past the row read zeros
-        auto request = [&](int slot, int64_t lo, int len) {
-            const uint32_t bytes = (uint32_t)len * 4u;
-            const __amdgpu_buffer_rsrc_t rc =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(a.col_idx + lo), 0, (int)bytes, 0x00020000);
-            const __amdgpu_buffer_rsrc_t rv =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.vals + lo), 0, (int)bytes, 0x00020000);
+        auto scout = [&](auto role_tag) {
+            constexpr bool MARKS = decltype(role_tag)::value;          // false: records, true: stamps and marks
+            int64_t redo_until = -1;         // steps up to this one re-read their values (they follow a very long row)
+            uint32_t er_col[kLead][kChunks], er_val[kLead][kChunks];
+            // entries of a row into ring slot `slot`; lanes past the row read zeros
+            auto request = [&](int slot, int64_t lo, int len) {
+                const uint32_t bytes = (uint32_t)len * 4u;
+                const __amdgpu_buffer_rsrc_t rc =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(a.col_idx + lo), 0, (int)bytes, 0x00020000);
 #pragma unroll
-            for (int c = 0; c < kChunks; ++c) {
-                er_col[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)(c * kWave + lane) * 4u, 0, 0);
-                er_val[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)(c * kWave + lane) * 4u, 0, 0);
-            }
-        };
+                for (int c = 0; c < kChunks; ++c) er_col[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)(c * kWave + lane) * 4u, 0, 0);
+                if constexpr (!MARKS) {
+                    const __amdgpu_buffer_rsrc_t rv =
+                        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.vals + lo), 0, (int)bytes, 0x00020000);
 #pragma unroll
-        for (int t = 0; t < kLead; ++t) request(t, lane_read_i64(lo_a, t), __builtin_amdgcn_readlane(len_a, t));
+                    for (int c = 0; c < kChunks; ++c) er_val[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)(c * kWave + lane) * 4u, 0, 0);
+                }
+            };
+#pragma unroll
+            for (int t = 0; t < kLead; ++t) request(t, lane_read_i64(lo_a, t), __builtin_amdgcn_readlane(len_a, t));
 
-        // One section: steps kG*i .. kG*i+kG-1.  HALF = i & 1 selects the entry-ring slots.
-        auto write_group = [&](int64_t i, auto half_tag) {
-            constexpr int HALF = decltype(half_tag)::value;
-            const int j0 = (int)((i * kG) & (kWave - 1));
-            const int64_t w = (i * kG) / kWave;
-            if (j0 == 0) {                       // a new window: rotate the tables, publish its scalars
-                if (w > 0) {
-                    s_w *= rho64;
-                    eos_w *= inv_rho64;
-                    lo_a = lo_b;
-                    len_a = len_b;
-                    y_a = y_b;
-                    load_window(w + 1, lo_b, len_b, y_b);
+            // One section: steps kG*i .. kG*i+kG-1.  HALF = i & 1 selects the entry-ring slots.
+            auto write_group = [&](int64_t i, auto half_tag) {
+                constexpr int HALF = decltype(half_tag)::value;
+                const int j0 = (int)((i * kG) & (kWave - 1));
+                const int64_t w = (i * kG) / kWave;
+                if (j0 == 0) {                       // a new window: rotate the tables, publish its scalars
+                    if (w > 0) {
+                        s_w *= rho64;
+                        eos_w *= inv_rho64;
+                        lo_a = lo_b;
+                        len_a = len_b;
+                        y_a = y_b;
+                        load_window(w + 1, lo_b, len_b, y_b);
+                    }
+                    if constexpr (!MARKS) {
+                        const double yd = (double)y_a;
+                        const double sl = yd * s_w * rho_pow, el = yd * eos_w * inv_rho_pow1;
+                        const bool live = w * kWave + lane < n;
+                        if constexpr (LOSS == kLossHinge) {
+                            sc_tab.zs = sl;
+                            sc_tab.cs = live ? el : 0.0;
+                        } else {
+                            sc_tab.zs = (float)(sl * 1.4426950408889634);
+                            sc_tab.cs = live ? (float)el : 0.0f;
+                        }
+                    }
                 }
-                const double yd = (double)y_a;
-                const double sl = yd * s_w * rho_pow, el = yd * eos_w * inv_rho_pow1;
-                const bool live = w * kWave + lane < n;
-                if constexpr (LOSS == kLossHinge) {
-                    sc_tab.zs = sl;
-                    sc_tab.cs = live ? el : 0.0;
-                } else {
-                    sc_tab.zs = (float)(sl * 1.4426950408889634);
-                    sc_tab.cs = live ? (float)el : 0.0f;
-                }
-            }
-            // the rows requested now lie kLead steps ahead: in this window while j0 + u + kLead < 64
-            const bool ahead_in_next = j0 + kLead >= kWave;
-            const int64_t lo_t = ahead_in_next ? lo_b : lo_a;
-            const int len_t = ahead_in_next ? len_b : len_a;
-            char *sec0 = lds + L::ring + (uint32_t)(i % kSections) * kSectionBytes;
-            char *sec = sec0 + lane * 16;
+                // the rows requested now lie kLead steps ahead: in this window while j0 + u + kLead < 64
+                const bool ahead_in_next = j0 + kLead >= kWave;
+                const int64_t lo_t = ahead_in_next ? lo_b : lo_a;
+                const int len_t = ahead_in_next ? len_b : len_a;
+                char *sec0 = lds + L::ring + (uint32_t)(i % kSections) * kSectionBytes;
+                char *sec = sec0 + lane * 16;
 #pragma unroll
-            for (int u = 0; u < kG; ++u) {
-                const int slot = HALF * kG + u;
-                const int len = __builtin_amdgcn_readlane(len_a, j0 + u);
+                for (int u = 0; u < kG; ++u) {
+                    const int slot = HALF * kG + u;
+                    const int len = __builtin_amdgcn_readlane(len_a, j0 + u);
+                    char *h = sec0 + u * kStepBytes + kRecordBytes;          // the step's scalars
+                    if constexpr (MARKS) {
+                        // Stamps: the step numbers of the last writes to the two slots of an HBM-resident
+                        // column (lanes without one use a slot of their own).  Read, compared and rewritten
+                        // in step order; all reads of a step go out before the first of them is waited for.
+                        const int64_t t = i * kG + u;
+                        const uint16_t now = (uint16_t)t;
+                        uint16_t *pa[kChunks], *pb[kChunks];
+                        bool is_tail[kChunks];
 #pragma unroll
-                for (int c = 0; c < kChunks; ++c) {
-                    const int e = c * kWave + lane;
-                    const uint32_t col = er_col[slot][c];
-                    const bool in = e < len;
-                    const bool is_head = in && col < (uint32_t)kPHead;
-                    const bool is_tail = in && col >= (uint32_t)kPHead;
-                    pu32x4 rec;
-                    rec[0] = er_val[slot][c];
-                    rec[1] = is_head ? L::head + col * (uint32_t)sizeof(TV) : L::head_scratch + e * (uint32_t)sizeof(TV);
-                    rec[2] = (is_tail ? col : (uint32_t)e) * (uint32_t)sizeof(TV);
-                    const uint32_t sa = is_tail ? stamp_slot_a(col) : (uint32_t)(kPStamps + e);
-                    const uint32_t sb = is_tail ? stamp_slot_b(col) : (uint32_t)(kPStamps + e);
-                    rec[3] = (sa * 2u) | (sb * 2u << 16) | (is_tail ? 0x80000000u : 0u);
-                    *reinterpret_cast<pu32x4 *>(sec + u * kStepBytes + c * (kWave * 16)) = rec;
+                        for (int c = 0; c < kChunks; ++c) {
+                            const int e = c * kWave + lane;
+                            const uint32_t col = er_col[slot][c];
+                            is_tail[c] = e < len && col >= (uint32_t)kPHead;
+                            pa[c] = reinterpret_cast<uint16_t *>(lds + L::stamp_a) + (is_tail[c] ? stamp_slot_a(col) : (uint32_t)(kPStamps + e));
+                            pb[c] = reinterpret_cast<uint16_t *>(lds + L::stamp_b) + (is_tail[c] ? stamp_slot_b(col) : (uint32_t)(kPStamps + e));
+                        }
+                        uint16_t sa[kChunks], sb[kChunks];
+#pragma unroll
+                        for (int c = 0; c < kChunks; ++c) {
+                            sa[c] = *pa[c];
+                            sb[c] = *pb[c];
+                        }
+                        bool recent = false;         // was one of this row's HBM-resident columns written in the last kRecent steps?
+#pragma unroll
+                        for (int c = 0; c < kChunks; ++c) {
+                            recent |= is_tail[c] & ((uint16_t)(now - sa[c]) < kRecent) & ((uint16_t)(now - sb[c]) < kRecent);
+                            *pa[c] = now;
+                            *pb[c] = now;
+                        }
+                        // a row too long for the records writes its excess columns without stamps: the steps
+                        // that could have fetched such a column early re-read instead
+                        if (len > kSlots) redo_until = t + kRecent - 1;
+                        const bool stale = __any(recent) || t <= redo_until;
+                        if (lane == 0) reinterpret_cast<StepRow *>(h + 16)->pad = stale ? 1 : 0;
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < kChunks; ++c) {
+                            const int e = c * kWave + lane;
+                            const uint32_t col = er_col[slot][c];
+                            const bool in = e < len;
+                            const bool is_head = in && col < (uint32_t)kPHead;
+                            const bool is_tail = in && col >= (uint32_t)kPHead;
+                            pu32x4 rec;
+                            rec[0] = er_val[slot][c];
+                            rec[1] = is_head ? L::head + col * (uint32_t)sizeof(TV) : L::head_scratch + e * (uint32_t)sizeof(TV);
+                            // lanes without an HBM-resident column point past the end of the vector: their
+                            // loads return zero and their stores are dropped, so they cause no traffic
+                            rec[2] = is_tail ? col * (uint32_t)sizeof(TV) : 0xFFFFFFF0u;
+                            rec[3] = is_tail ? 0x80000000u : 0u;
+                            *reinterpret_cast<pu32x4 *>(sec + u * kStepBytes + c * (kWave * 16)) = rec;
+                        }
+                        if (lane == j0 + u) {        // the lane that holds this step's scalars publishes them
+                            *reinterpret_cast<StepScalars<TV> *>(h) = sc_tab;
+                            reinterpret_cast<StepRow *>(h + 16)->lo = lo_a;
+                            reinterpret_cast<StepRow *>(h + 16)->len = len_a;
+                        }
+                    }
+                    const int jj = (j0 + u + kLead) & (kWave - 1);
+                    request(slot, lane_read_i64(lo_t, jj), __builtin_amdgcn_readlane(len_t, jj));
                 }
-                if (lane == j0 + u) {            // the lane that holds this step's scalars publishes them
-                    StepRow sr;
-                    sr.lo = lo_a;
-                    sr.len = len_a;
-                    sr.pad = 0;
-                    char *h = sec0 + u * kStepBytes + kRecordBytes;
-                    *reinterpret_cast<StepScalars<TV> *>(h) = sc_tab;
-                    *reinterpret_cast<StepRow *>(h + 16) = sr;
+            };
+            for (int64_t i = 0; i <= ngroups; i += 2) {
+                write_group(i, std::integral_constant<int, 0>{});
+                wait_lds_then_barrier();
+                if (i + 1 <= ngroups) {
+                    write_group(i + 1, std::integral_constant<int, 1>{});
+                    wait_lds_then_barrier();
                 }
-                const int jj = (j0 + u + kLead) & (kWave - 1);
-                request(slot, lane_read_i64(lo_t, jj), __builtin_amdgcn_readlane(len_t, jj));
             }
         };
-        for (int64_t i = 0; i <= ngroups; i += 2) {
-            write_group(i, std::integral_constant<int, 0>{});
-            wait_lds_then_barrier();
-            if (i + 1 <= ngroups) {
-                write_group(i + 1, std::integral_constant<int, 1>{});
-                wait_lds_then_barrier();
-            }
-        }
+        if (wave == 1) scout(std::false_type{});
+        else scout(std::true_type{});
     } else {
         // ------------------------------------------------------------------------- worker
         const __amdgpu_buffer_rsrc_t vres =
@@ -324,7 +364,7 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
         pu32x4 rec[kG][kChunks];
         TV vr[kG][kChunks];
         StepScalars<TV> scr[kG];
-        int lenr[kG];
+        int lenr[kG], staler[kG];
         const char *ring0 = lds + L::ring;
         const char *ring = ring0 + lane * 16;
 
@@ -339,6 +379,7 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
         for (int q = 0; q <= kTQ; ++q) {
             scr[q] = *reinterpret_cast<const StepScalars<TV> *>(ring0 + q * kStepBytes + kRecordBytes);
             lenr[q] = reinterpret_cast<const StepRow *>(ring0 + q * kStepBytes + kRecordBytes + 16)->len;
+            staler[q] = reinterpret_cast<const StepRow *>(ring0 + q * kStepBytes + kRecordBytes + 16)->pad;
         }
 #pragma unroll
         for (int q = 0; q < kTQ; ++q)
@@ -356,16 +397,9 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                 const char *hdr_t = ring0 + off_cur + u * kStepBytes + kRecordBytes;      // scalars of step t
                 // Model values and stamps of step t first: they queue right behind the previous
                 // step's LDS writes and everything below waits for them.
-                const uint16_t now = (uint16_t)t;
                 TV hv[kChunks];
-                uint16_t sa[kChunks], sb[kChunks];
 #pragma unroll
-                for (int c = 0; c < kChunks; ++c) {
-                    const pu32x4 r = rec[u][c];
-                    hv[c] = *reinterpret_cast<const TV *>(lds + r[1]);
-                    sa[c] = *reinterpret_cast<const uint16_t *>(lds + L::stamp_a + (r[3] & 0xffffu));
-                    sb[c] = *reinterpret_cast<const uint16_t *>(lds + L::stamp_b + ((r[3] >> 16) & 0x7fffu));
-                }
+                for (int c = 0; c < kChunks; ++c) hv[c] = *reinterpret_cast<const TV *>(lds + rec[u][c][1]);
                 {   // records and scalars of step t+kTQ+1
                     const int uu = u + kTQ + 1;
                     const uint32_t src = (uu < kG ? off_cur : off_nxt) + (uu % kG) * kStepBytes;
@@ -374,6 +408,7 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                         rec[uu % kG][c] = *reinterpret_cast<const pu32x4 *>(ring + src + c * (kWave * 16));
                     scr[uu % kG] = *reinterpret_cast<const StepScalars<TV> *>(ring0 + src + kRecordBytes);
                     lenr[uu % kG] = reinterpret_cast<const StepRow *>(ring0 + src + kRecordBytes + 16)->len;
+                    staler[uu % kG] = reinterpret_cast<const StepRow *>(ring0 + src + kRecordBytes + 16)->pad;
                 }
                 if (t < n) {
                     const StepScalars<TV> sc = scr[u];
@@ -381,17 +416,14 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                     TV vv[kChunks];
                     float val[kChunks];
                     bool tail[kChunks];
-                    bool stale = false;
 #pragma unroll
                     for (int c = 0; c < kChunks; ++c) {
                         const pu32x4 r = rec[u][c];
                         val[c] = __uint_as_float(r[0]);
                         tail[c] = (int32_t)r[3] < 0;
-                        // evaluated for every lane (no short circuit: nothing here sits under a branch)
-                        stale |= tail[c] & ((uint16_t)(now - sa[c]) < kRecent) & ((uint16_t)(now - sb[c]) < kRecent);
                         vv[c] = tail[c] ? vr[u][c] : hv[c];
                     }
-                    if (__any(stale)) {             // drain, then read this step's HBM-resident values again
+                    if (__builtin_amdgcn_readfirstlane(staler[u]) != 0) {      // (the scout's verdict) drain, then read this step's HBM-resident values again
 #pragma unroll
                         for (int c = 0; c < kChunks; ++c) {
                             const TV fresh = drained_buffer_load(vdesc, rec[u][c][2], TV{});
@@ -410,7 +442,7 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                             const float xv = __uint_as_float(drained_global_load_u32(a.vals + (in ? lo + e : lo)));
                             const bool hd = xc < (uint32_t)kPHead;
                             const TV cur = (in && hd) ? head[xc]
-                                                      : drained_buffer_load(vdesc, (in ? xc : (uint32_t)lane) * (uint32_t)sizeof(TV), TV{});
+                                                      : drained_buffer_load(vdesc, in ? xc * (uint32_t)sizeof(TV) : 0xFFFFFFF0u, TV{});
                             if (in) acc += cur * (TV)xv;
                         }
                     }
@@ -426,8 +458,6 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                         const pu32x4 r = rec[u][c];
                         const TV nv = vv[c] + coef * (TV)val[c];
                         *reinterpret_cast<TV *>(lds + r[1]) = nv;
-                        *reinterpret_cast<uint16_t *>(lds + L::stamp_a + (r[3] & 0xffffu)) = now;
-                        *reinterpret_cast<uint16_t *>(lds + L::stamp_b + ((r[3] >> 16) & 0x7fffu)) = now;
                         store_state(vres, r[2], nv);
                     }
                     if (len > kSlots) {
@@ -440,13 +470,9 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
                             if (in && xc < (uint32_t)kPHead) {
                                 head[xc] += coef * (TV)xv;
                             } else {
-                                const uint32_t off = (in ? xc : (uint32_t)lane) * (uint32_t)sizeof(TV);
+                                const uint32_t off = in ? xc * (uint32_t)sizeof(TV) : 0xFFFFFFF0u;      // (past the end: no access)
                                 const TV cur = drained_buffer_load(vdesc, off, TV{});
                                 drained_buffer_store(vdesc, off, in ? cur + coef * (TV)xv : cur);
-                                if (in) {
-                                    reinterpret_cast<uint16_t *>(lds + L::stamp_a)[stamp_slot_a(xc)] = now;
-                                    reinterpret_cast<uint16_t *>(lds + L::stamp_b)[stamp_slot_b(xc)] = now;
-                                }
                             }
                         }
                     }
@@ -461,25 +487,69 @@ __global__ __launch_bounds__(2 * kWave) void chain_csr_pair_kernel(ChainArgs a)
     }
     __syncthreads();
 
-    // w = s*v at the chain's end: s = (1-eta*lambda)^n by binary powering in fp64
+    // the columns kept in LDS go back to the vector in the workspace
+    for (int c = tid; c < kPHead && c < d; c += kPairThreads) v[c] = head[c];
+}
+
+// Before the chains: every chain's vector in the workspace starts as the common start vector (or
+// zero).  Grid row y is chain row0 + y; the workgroups of a row share its columns.
+template <typename TV>
+__global__ __launch_bounds__(256) void csr_state_start_kernel(TV *state, const float *w_start, int64_t d, int row0)
+{
+    TV *v = state + (int64_t)(row0 + (int)blockIdx.y) * d;
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < d; c += (int64_t)gridDim.x * 256)
+        v[c] = w_start ? (TV)w_start[c] : (TV)0;
+}
+
+// After the chains: W[chain,:] = (1-eta*lambda)^n * v, the lazy scale applied once, in fp64.  Grid row
+// y is the chain that workgroup row0 + y of the chain kernel ran.
+template <typename TV>
+__global__ __launch_bounds__(256) void csr_state_finish_kernel(const TV *state, float *W, const int32_t *order,
+                                                                const int64_t *nsteps, double rho, int64_t d, int row0)
+{
+    const int b = row0 + (int)blockIdx.y;
+    const int chain = order[b];
     double s_end = 1.0, p = rho;
-    for (int64_t e = n; e > 0; e >>= 1) {
+    for (int64_t e = nsteps[b]; e > 0; e >>= 1) {       // (uniform over the workgroup)
         if (e & 1) s_end *= p;
         p *= p;
     }
-    for (int c = tid; c < kPHead && c < d; c += 2 * kWave) out[c] = (float)(s_end * (double)head[c]);
-    for (int64_t c = kPHead + tid; c < d; c += 2 * kWave) out[c] = (float)(s_end * (double)v[c]);
+    const TV *v = state + (int64_t)chain * d;
+    float *out = W + (int64_t)chain * d;
+    for (int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x; c < d; c += (int64_t)gridDim.x * 256)
+        out[c] = (float)(s_end * (double)v[c]);
+}
+
+template <typename TV, int LOSS>
+static hipError_t launch_pair(const ChainArgs &a, hipStream_t s)
+{
+    TV *state = static_cast<TV *>(a.state);
+    constexpr int kRows = 32768;                // chains per launch of the start and finish kernels (a grid's y extent is 16 bits)
+    // enough workgroups per chain to fill the device, not more than a chain has 256-column strips
+    const int rows_at_once = a.k < kRows ? a.k : kRows;
+    const unsigned across = (unsigned)std::max<int64_t>(1, std::min<int64_t>((a.d + 255) / 256, (4096 + rows_at_once - 1) / rows_at_once));
+    for (int row0 = 0; row0 < a.k; row0 += kRows) {
+        const unsigned rows = (unsigned)std::min(kRows, a.k - row0);
+        hipLaunchKernelGGL((csr_state_start_kernel<TV>), dim3(across, rows), dim3(256), 0, s, state, a.w_start, a.d, row0);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((chain_csr_pair_kernel<LOSS>), dim3(a.k), dim3(kPairThreads), 0, s, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    for (int row0 = 0; row0 < a.k; row0 += kRows) {
+        const unsigned rows = (unsigned)std::min(kRows, a.k - row0);
+        hipLaunchKernelGGL((csr_state_finish_kernel<TV>), dim3(across, rows), dim3(256), 0, s, state, a.W, a.order, a.nsteps, a.rho,
+                           a.d, row0);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_csr_pair(const Plan &p, const ChainArgs &a, hipStream_t s)
 {
-    if (p.loss == WPSGD_HINGE)
-        hipLaunchKernelGGL((chain_csr_pair_kernel<kLossHinge>), dim3(a.k), dim3(2 * kWave), 0, s, a);
-    else
-        hipLaunchKernelGGL((chain_csr_pair_kernel<kLossLogistic>), dim3(a.k), dim3(2 * kWave), 0, s, a);
-    return hipGetLastError();
+    return p.loss == WPSGD_HINGE ? launch_pair<double, kLossHinge>(a, s) : launch_pair<float, kLossLogistic>(a, s);
 }
 
 }  // namespace wpsgd
