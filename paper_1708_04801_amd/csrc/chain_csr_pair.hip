@@ -60,6 +60,7 @@ constexpr uint32_t kRecordBytes = kSlots * 16;              // the records of on
 constexpr uint32_t kStepBytes = kRecordBytes + 32;          // ... followed by its scalars (StepScalars, StepRow)
 constexpr uint32_t kSectionBytes = kG * kStepBytes;
 constexpr uint16_t kRecent = 2 * kTQ;
+constexpr int kWideTail = 1 << 30;  // flag in a step's row length: HBM-resident columns also outside chunk 0
 static_assert(kTQ + 1 < kG, "record and value rings are indexed modulo kG");
 static_assert(kLead == 2 * kG, "the scout's entry ring is two sections deep");
 
@@ -228,19 +229,26 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
         auto scout = [&](auto role_tag) {
             constexpr bool MARKS = decltype(role_tag)::value;          // false: records, true: stamps and marks
             int64_t redo_until = -1;         // steps up to this one re-read their values (they follow a very long row)
+            struct { bool tail, forced; uint16_t now, sa, sb; char *h; } prev = {false, false, 0, 0, 0, nullptr};      // (stamp scout) the step before
             uint32_t er_col[kLead][kChunks], er_val[kLead][kChunks];
-            // entries of a row into ring slot `slot`; lanes past the row read zeros
+            // Entries of a row into ring slot `slot`, last entry first: slot position e (lane e % 64 of
+            // chunk e / 64) holds entry len-1-e.  Columns ascend within a row, so the HBM-resident ones
+            // (the large ones) end up at the front and chunk 0 holds them all unless the row has more
+            // than 64 of them: the worker then needs one load and one store to HBM per step, not two of
+            // each.  Positions past the row's start get an offset past the end and read zeros.
             auto request = [&](int slot, int64_t lo, int len) {
                 const uint32_t bytes = (uint32_t)len * 4u;
                 const __amdgpu_buffer_rsrc_t rc =
                     __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(a.col_idx + lo), 0, (int)bytes, 0x00020000);
 #pragma unroll
-                for (int c = 0; c < kChunks; ++c) er_col[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)(c * kWave + lane) * 4u, 0, 0);
+                for (int c = 0; c < kChunks; ++c)
+                    er_col[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rc, (uint32_t)(len - 1 - (c * kWave + lane)) * 4u, 0, 0);
                 if constexpr (!MARKS) {
                     const __amdgpu_buffer_rsrc_t rv =
                         __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.vals + lo), 0, (int)bytes, 0x00020000);
 #pragma unroll
-                    for (int c = 0; c < kChunks; ++c) er_val[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)(c * kWave + lane) * 4u, 0, 0);
+                    for (int c = 0; c < kChunks; ++c)
+                        er_val[slot][c] = __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)(len - 1 - (c * kWave + lane)) * 4u, 0, 0);
                 }
             };
 #pragma unroll
@@ -286,39 +294,52 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                     char *h = sec0 + u * kStepBytes + kRecordBytes;          // the step's scalars
                     if constexpr (MARKS) {
                         // Stamps: the step numbers of the last writes to the two slots of an HBM-resident
-                        // column (lanes without one use a slot of their own).  Read, compared and rewritten
-                        // in step order; all reads of a step go out before the first of them is waited for.
+                        // column (lanes without one use a slot of their own), read, compared and rewritten
+                        // in step order.  What is written does not depend on what was read, so a step's reads
+                        // and writes go out back to back and the comparison is made one step later, when the
+                        // values have arrived: the wave never waits for LDS.  Chunk 0 holds all HBM-resident
+                        // columns of a row unless there are more than 64 (then the others are done on the spot).
                         const int64_t t = i * kG + u;
                         const uint16_t now = (uint16_t)t;
-                        uint16_t *pa[kChunks], *pb[kChunks];
-                        bool is_tail[kChunks];
+                        const int e0 = lane;
+                        const uint32_t col0 = er_col[slot][0];
+                        const bool tail0 = e0 < len && col0 >= (uint32_t)kPHead;
+                        uint16_t *const pa = reinterpret_cast<uint16_t *>(lds + L::stamp_a) + (tail0 ? stamp_slot_a(col0) : (uint32_t)(kPStamps + e0));
+                        uint16_t *const pb = reinterpret_cast<uint16_t *>(lds + L::stamp_b) + (tail0 ? stamp_slot_b(col0) : (uint32_t)(kPStamps + e0));
+                        const uint16_t sa = *pa, sb = *pb;
+                        *pa = now;
+                        *pb = now;
+                        bool more = false;           // recent writes to HBM-resident columns outside chunk 0
 #pragma unroll
-                        for (int c = 0; c < kChunks; ++c) {
+                        for (int c = 1; c < kChunks; ++c) {
                             const int e = c * kWave + lane;
                             const uint32_t col = er_col[slot][c];
-                            is_tail[c] = e < len && col >= (uint32_t)kPHead;
-                            pa[c] = reinterpret_cast<uint16_t *>(lds + L::stamp_a) + (is_tail[c] ? stamp_slot_a(col) : (uint32_t)(kPStamps + e));
-                            pb[c] = reinterpret_cast<uint16_t *>(lds + L::stamp_b) + (is_tail[c] ? stamp_slot_b(col) : (uint32_t)(kPStamps + e));
-                        }
-                        uint16_t sa[kChunks], sb[kChunks];
-#pragma unroll
-                        for (int c = 0; c < kChunks; ++c) {
-                            sa[c] = *pa[c];
-                            sb[c] = *pb[c];
-                        }
-                        bool recent = false;         // was one of this row's HBM-resident columns written in the last kRecent steps?
-#pragma unroll
-                        for (int c = 0; c < kChunks; ++c) {
-                            recent |= is_tail[c] & ((uint16_t)(now - sa[c]) < kRecent) & ((uint16_t)(now - sb[c]) < kRecent);
-                            *pa[c] = now;
-                            *pb[c] = now;
+                            const bool tl = e < len && col >= (uint32_t)kPHead;
+                            if (__builtin_expect(__any(tl), 0)) {
+                                uint16_t *const qa = reinterpret_cast<uint16_t *>(lds + L::stamp_a) + (tl ? stamp_slot_a(col) : (uint32_t)(kPStamps + e));
+                                uint16_t *const qb = reinterpret_cast<uint16_t *>(lds + L::stamp_b) + (tl ? stamp_slot_b(col) : (uint32_t)(kPStamps + e));
+                                const uint16_t ta = *qa, tb = *qb;
+                                more |= __any(tl & ((uint16_t)(now - ta) < kRecent) & ((uint16_t)(now - tb) < kRecent));
+                                *qa = now;
+                                *qb = now;
+                            }
                         }
                         // a row too long for the records writes its excess columns without stamps: the steps
                         // that could have fetched such a column early re-read instead
                         if (len > kSlots) redo_until = t + kRecent - 1;
-                        const bool stale = __any(recent) || t <= redo_until;
-                        if (lane == 0) reinterpret_cast<StepRow *>(h + 16)->pad = stale ? 1 : 0;
+                        const bool forced = more || t <= redo_until;
+                        // the verdict on the step before this one (its stamps have arrived by now)
+                        if (u > 0) {                 // (a section's last step was settled before its barrier)
+                            const bool stale = __any(prev.tail & ((uint16_t)(prev.now - prev.sa) < kRecent) & ((uint16_t)(prev.now - prev.sb) < kRecent)) || prev.forced;
+                            if (lane == 0) reinterpret_cast<StepRow *>(prev.h + 16)->pad = stale ? 1 : 0;
+                        }
+                        prev.tail = tail0; prev.now = now; prev.sa = sa; prev.sb = sb; prev.forced = forced; prev.h = h;
+                        if (u == kG - 1) {           // the section's last step is settled before the barrier
+                            const bool stale = __any(tail0 & ((uint16_t)(now - sa) < kRecent) & ((uint16_t)(now - sb) < kRecent)) || forced;
+                            if (lane == 0) reinterpret_cast<StepRow *>(h + 16)->pad = stale ? 1 : 0;
+                        }
                     } else {
+                        bool far_tail = false;       // an HBM-resident column outside chunk 0?
 #pragma unroll
                         for (int c = 0; c < kChunks; ++c) {
                             const int e = c * kWave + lane;
@@ -326,6 +347,7 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                             const bool in = e < len;
                             const bool is_head = in && col < (uint32_t)kPHead;
                             const bool is_tail = in && col >= (uint32_t)kPHead;
+                            if (c > 0) far_tail |= is_tail;
                             pu32x4 rec;
                             rec[0] = er_val[slot][c];
                             rec[1] = is_head ? L::head + col * (uint32_t)sizeof(TV) : L::head_scratch + e * (uint32_t)sizeof(TV);
@@ -335,10 +357,11 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                             rec[3] = is_tail ? 0x80000000u : 0u;
                             *reinterpret_cast<pu32x4 *>(sec + u * kStepBytes + c * (kWave * 16)) = rec;
                         }
+                        const bool wide = __any(far_tail);
                         if (lane == j0 + u) {        // the lane that holds this step's scalars publishes them
                             *reinterpret_cast<StepScalars<TV> *>(h) = sc_tab;
                             reinterpret_cast<StepRow *>(h + 16)->lo = lo_a;
-                            reinterpret_cast<StepRow *>(h + 16)->len = len_a;
+                            reinterpret_cast<StepRow *>(h + 16)->len = len_a | (wide ? kWideTail : 0);
                         }
                     }
                     const int jj = (j0 + u + kLead) & (kWave - 1);
@@ -362,7 +385,7 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
             __builtin_amdgcn_make_buffer_rsrc(v, 0, (int)(uint32_t)(d * (int64_t)sizeof(TV)), 0x00020000);
         const pu32x4 vdesc = descriptor(v, (uint32_t)(d * (int64_t)sizeof(TV)));
         pu32x4 rec[kG][kChunks];
-        TV vr[kG][kChunks];
+        TV vr[kG];                    // HBM-resident values of chunk 0 (the other chunks hold none, or the step is flagged)
         StepScalars<TV> scr[kG];
         int lenr[kG], staler[kG];
         const char *ring0 = lds + L::ring;
@@ -382,9 +405,7 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
             staler[q] = reinterpret_cast<const StepRow *>(ring0 + q * kStepBytes + kRecordBytes + 16)->pad;
         }
 #pragma unroll
-        for (int q = 0; q < kTQ; ++q)
-#pragma unroll
-            for (int c = 0; c < kChunks; ++c) vr[q][c] = load_state(vres, rec[q][c][2], TV{});
+        for (int q = 0; q < kTQ; ++q) vr[q] = load_state(vres, rec[q][0][2], TV{});
         __builtin_amdgcn_s_waitcnt(0x0F70);      // enter the loop with an empty queue
 
         for (int64_t g = 0; g < ngroups; ++g) {
@@ -410,9 +431,14 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                     lenr[uu % kG] = reinterpret_cast<const StepRow *>(ring0 + src + kRecordBytes + 16)->len;
                     staler[uu % kG] = reinterpret_cast<const StepRow *>(ring0 + src + kRecordBytes + 16)->pad;
                 }
-                if (t < n) {
+                // (Steps past the chain's end run like any other: their step scalar is zero, so they write
+                // back what they read.  A branch around them would keep the compiler from moving the reads
+                // above to the front of the step.)
+                {
                     const StepScalars<TV> sc = scr[u];
-                    const int len = __builtin_amdgcn_readfirstlane(lenr[u]);
+                    const int len_word = __builtin_amdgcn_readfirstlane(lenr[u]);
+                    const int len = len_word & (kWideTail - 1);
+                    const bool wide = (len_word & kWideTail) != 0;
                     TV vv[kChunks];
                     float val[kChunks];
                     bool tail[kChunks];
@@ -421,11 +447,16 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                         const pu32x4 r = rec[u][c];
                         val[c] = __uint_as_float(r[0]);
                         tail[c] = (int32_t)r[3] < 0;
-                        vv[c] = tail[c] ? vr[u][c] : hv[c];
+                        vv[c] = hv[c];
                     }
-                    if (__builtin_amdgcn_readfirstlane(staler[u]) != 0) {      // (the scout's verdict) drain, then read this step's HBM-resident values again
+                    vv[0] = tail[0] ? vr[u] : hv[0];
+                    if (__builtin_expect(__builtin_amdgcn_readfirstlane(staler[u]) != 0, 0)) {      // (the scout's verdict) drain, then read this step's HBM-resident values again
+                        const TV fresh = drained_buffer_load(vdesc, rec[u][0][2], TV{});
+                        if (tail[0]) vv[0] = fresh;
+                    }
+                    if (__builtin_expect(wide, 0)) {        // more than 64 HBM-resident columns: the others are read here, after everything before
 #pragma unroll
-                        for (int c = 0; c < kChunks; ++c) {
+                        for (int c = 1; c < kChunks; ++c) {
                             const TV fresh = drained_buffer_load(vdesc, rec[u][c][2], TV{});
                             if (tail[c]) vv[c] = fresh;
                         }
@@ -433,11 +464,11 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                     TV acc = (TV)0;
 #pragma unroll
                     for (int c = 0; c < kChunks; ++c) acc += vv[c] * (TV)val[c];
-                    if (len > kSlots) {             // the rest of a very long row, one entry per lane at a time
+                    if (__builtin_expect(len > kSlots, 0)) {             // the rest of a very long row, one entry per lane at a time
                         const int64_t lo = reinterpret_cast<const StepRow *>(hdr_t + 16)->lo;
-                        for (int e0 = kSlots; e0 < len; e0 += kWave) {
+                        for (int e0 = 0; e0 < len - kSlots; e0 += kWave) {      // (the records hold the row's last kSlots entries)
                             const int e = e0 + lane;
-                            const bool in = e < len;
+                            const bool in = e < len - kSlots;
                             const uint32_t xc = drained_global_load_u32(a.col_idx + (in ? lo + e : lo));
                             const float xv = __uint_as_float(drained_global_load_u32(a.vals + (in ? lo + e : lo)));
                             const bool hd = xc < (uint32_t)kPHead;
@@ -458,13 +489,14 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                         const pu32x4 r = rec[u][c];
                         const TV nv = vv[c] + coef * (TV)val[c];
                         *reinterpret_cast<TV *>(lds + r[1]) = nv;
-                        store_state(vres, r[2], nv);
+                        if (c == 0) store_state(vres, r[2], nv);
+                        else if (__builtin_expect(wide, 0)) drained_buffer_store(vdesc, r[2], nv);
                     }
-                    if (len > kSlots) {
+                    if (__builtin_expect(len > kSlots, 0)) {
                         const int64_t lo = reinterpret_cast<const StepRow *>(hdr_t + 16)->lo;
-                        for (int e0 = kSlots; e0 < len; e0 += kWave) {
+                        for (int e0 = 0; e0 < len - kSlots; e0 += kWave) {
                             const int e = e0 + lane;
-                            const bool in = e < len;
+                            const bool in = e < len - kSlots;
                             const uint32_t xc = drained_global_load_u32(a.col_idx + (in ? lo + e : lo));
                             const float xv = __uint_as_float(drained_global_load_u32(a.vals + (in ? lo + e : lo)));
                             if (in && xc < (uint32_t)kPHead) {
@@ -478,9 +510,7 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
                     }
                 }
                 // HBM-resident values of step t+kTQ (its records arrived one step ago)
-#pragma unroll
-                for (int c = 0; c < kChunks; ++c)
-                    vr[(u + kTQ) % kG][c] = load_state(vres, rec[(u + kTQ) % kG][c][2], TV{});
+                vr[(u + kTQ) % kG] = load_state(vres, rec[(u + kTQ) % kG][0][2], TV{});
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);      // all stores done before the vector is read back
