@@ -216,7 +216,12 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
         int len_a, len_b;
         float y_a, y_b;
         auto load_window = [&](int64_t w, int64_t &lo, int &len, float &y) {
-            const uint32_t row = sample_window(seed_lo, seed_hi, (uint32_t)chain, step0 + w * kWave, m32, a.perm, (uint32_t)a.k);
+            // (The sampler is written out here rather than called: after a call the compiler no longer knows
+            // which loads are outstanding and drains the whole queue at the top of every iteration of the loop
+            // below, rows requested kLead steps ahead included.)
+            const uint64_t step = (uint64_t)(step0 + w * kWave + lane);
+            const uint32_t row = a.perm ? a.perm[shard_position((uint32_t)chain, (uint32_t)a.k, step, m32)]
+                                        : sample_row(seed_lo, seed_hi, (uint32_t)chain, step, m32);
             const int64_t p0 = a.row_ptr[row], p1 = a.row_ptr[(int64_t)row + 1];
             lo = p0;
             len = (int)(p1 - p0);
@@ -253,6 +258,9 @@ __global__ __launch_bounds__(kPairThreads) void chain_csr_pair_kernel(ChainArgs 
             };
 #pragma unroll
             for (int t = 0; t < kLead; ++t) request(t, lane_read_i64(lo_a, t), __builtin_amdgcn_readlane(len_a, t));
+            // Enter the loop with an empty queue: with loads pending on entry the compiler covers the entry
+            // path by a full drain in front of the loop's first use, which every iteration then pays.
+            __builtin_amdgcn_s_waitcnt(0x0F70);
 
             // One section: steps kG*i .. kG*i+kG-1.  HALF = i & 1 selects the entry-ring slots.
             auto write_group = [&](int64_t i, auto half_tag) {
