@@ -65,6 +65,9 @@ def lib():
         L.oracle_objective.argtypes = [vp, i32, pi64, pi32, pf32, i64, i64, pf32, pf64, f64, i32, pf64, pf64]
         L.oracle_run_chains.argtypes = [vp, i32, pi64, pi32, pf32, i64, i64, pf32, i64, pi64, pi64,
                                         f64, f64, i32, i32, ctypes.c_uint64, f64, i32, pf64, pf64]
+        L.oracle_check_triple.argtypes = [f64, f64, f64, f64, f64, f64, pf64]
+        L.oracle_delay_sgd_dense.argtypes = [vp, i32, i64, i64, pf32, pi64, i64, f64, f64, i32, i32, i32,
+                                             pf64, pi64, pf64]
         _lib = L
     return _lib
 
@@ -255,6 +258,43 @@ def run_spans(X, y, steps_per_span, n_spans, eta, lam, loss, seed, w0=None, shar
             W[i], _ = sgd(X, y, idx, eta, lam, loss, w0=v, csr_mode=csr_mode)
         v = combine(W, a)
     return v
+
+
+def check_triple(La, Lb, Lc, pa, pb, rate):
+    """Algorithm 4 on one triple of consecutive iterates: projections La, Lb, Lc on the sample and the
+    squared perpendicular lengths pa, pb of the two older ones.  Returns (accepted, gap)."""
+    gap = ctypes.c_double(0.0)
+    ok = lib().oracle_check_triple(float(La), float(Lb), float(Lc), float(pa), float(pb), float(rate),
+                                   ctypes.byref(gap))
+    return bool(ok), gap.value
+
+
+def delay_sgd(X, y, idx, eta, lam, loss, tau, w0=None, check=True):
+    """One server of Algorithm 3 (delay SGD with the Check function of Algorithm 4) over the explicit
+    visit order idx.  Returns (last accepted iterate, number of accepted updates, closest tie)."""
+    assert isinstance(X, Dense)
+    y = _y32(y)
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    w = np.zeros(X.d, dtype=np.float64) if w0 is None else np.array(w0, dtype=np.float64).copy()
+    acc, gap = ctypes.c_int64(0), ctypes.c_double(0.0)
+    _check(lib().oracle_delay_sgd_dense(X.data.ctypes.data, X.xtype, X.m, X.d, _p(y, ctypes.c_float),
+                                        _p(idx, ctypes.c_int64), idx.size, float(eta), float(lam), int(loss),
+                                        int(tau), int(bool(check)), _p(w, ctypes.c_double), ctypes.byref(acc),
+                                        ctypes.byref(gap)), "delay_sgd")
+    return w, int(acc.value), gap.value
+
+
+def run_delay_chains(X, y, n_samples, eta, lam, loss, seed, tau, check=True):
+    """All servers of Algorithm 3, phase 1: server i consumes n_samples[i] samples of its own stream.
+    Returns (W [k x d], accepted [k], closest tie [k])."""
+    n = np.ascontiguousarray(n_samples, dtype=np.int64)
+    W = np.zeros((n.size, X.d), dtype=np.float64)
+    acc = np.zeros(n.size, dtype=np.int64)
+    gap = np.zeros(n.size, dtype=np.float64)
+    for i in range(n.size):
+        W[i], acc[i], gap[i] = delay_sgd(X, y, sample_indices(seed, i, 0, int(n[i]), X.m), eta, lam, loss, tau,
+                                         check=check)
+    return W, acc, gap
 
 
 def wpsgd(X, y, n_steps, eta, lam, loss, seed, threads=None):

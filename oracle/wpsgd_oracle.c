@@ -14,6 +14,7 @@
  *     with T_i the delay of chain i behind the fastest chain (Table I)
  *   - weight_i = r^{T_i} / sum_j r^{T_j} for a chosen contraction rate r    (Eq. 8)
  *   - benefit condition  2 sum_i rate^{T_i} > sqrt(k) + k      (Eq. 7 / Eq. 9, Cor. 3/4)
+ *   - delayed-gradient server with its acceptance test    (Algorithms 3 and 4, Lemma 4)
  *
  * The paper does not define how a chain picks its n-th example beyond
  * "partition, shuffle, take the n-th"; this implementation replaces that by a
@@ -24,7 +25,9 @@
  *
  * Parity pins live in tests/test_oracle_pins.py (known-answer Philox vectors,
  * hand-computed weights, closed forms of the SGD recursion, finite-difference
- * gradient checks, brute force).  Parity unpinned: nothing in this file.
+ * gradient checks, brute force; for Algorithms 3/4 the scalar recurrence printed in the proof of
+ * Lemma 4, the reduction to Eq. 5 at delay 0, and hand cases of the acceptance test).  Parity
+ * unpinned: nothing in this file.
  *
  * Build: gcc -O2 -std=c11 -shared -fPIC -pthread wpsgd_oracle.c -o libwpsgd_oracle.so -lm
  */
@@ -376,6 +379,141 @@ int oracle_objective(const void *X, int xtype,
     }
     if (objective) *objective = 0.5 * lambda * sq + total / (double)m;
     if (error_rate) *error_rate = (double)wrong / (double)m;
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* WP-SGD with delay SGD (Section IV, Algorithms 3 and 4, Lemma 4).    */
+/*                                                                    */
+/* One server (chain) keeps the accepted iterates w_0, w_1, ..., w_J.  */
+/* For every sample x (label y) it receives, the gradient has been     */
+/* evaluated tau iterates ago (proof of Lemma 4):                      */
+/*     cand = w_J - eta*lambda*w_{J-tau} - eta*u(w_{J-tau}.x)*x,       */
+/* u = dL/dyhat; an iterate before the start is the start vector.      */
+/* The candidate becomes w_{J+1} only if the Check function accepts;   */
+/* otherwise it is abandoned and the next sample is tried.             */
+/*                                                                    */
+/* Check, for a triple (a, b, c) of consecutive iterates and the       */
+/* sample x, with beta^2 = x.x and the projections L_w = x.w:          */
+/*     rate  = (eta*lambda + c_star*eta*beta^2)^(1/tau)                */
+/*     L_min = (L_b - rate*L_a) / (1 - rate)                           */
+/*     accept iff L_c lies between L_min and L_b (ends included) and   */
+/*     the part of b perpendicular to x is not longer than that of a.  */
+/* The algorithm calls it on the iterates the delayed gradient spans   */
+/* (before the update) and on (w_{J-1}, w_J, cand) (after it).         */
+/* Readings taken where the listing is garbled or silent:              */
+/* c_star = 1 (both losses have |dL/dyhat| <= 1); the                  */
+/* tau-th root is taken with max(tau, 1); rate >= 1 rejects; the       */
+/* perpendicular test follows the proof (the older iterate's           */
+/* perpendicular part must be at least the newer's; the listing prints */
+/* the opposite inequality), on squared lengths |w|^2 - L_w^2/beta^2;  */
+/* a triple is tested only if all three iterates exist (no test        */
+/* reaches before w_0), so the first update is always accepted;        */
+/* the first call tests the triples inside w_{J-tau} .. w_J.           */
+/* ------------------------------------------------------------------ */
+
+/* One triple of Algorithm 4.  pa, pb: squared lengths of the parts of a and b perpendicular to
+ * the sample.  *gap (if not NULL) receives how far the closest comparison was from a tie,
+ * relative to the numbers compared. */
+int oracle_check_triple(double La, double Lb, double Lc, double pa, double pb, double rate, double *gap)
+{
+    if (!(rate < 1.0)) {
+        if (gap) *gap = INFINITY;
+        return 0;
+    }
+    const double Lmin = (Lb - rate * La) / (1.0 - rate);
+    const double lo = Lmin < Lb ? Lmin : Lb, hi = Lmin < Lb ? Lb : Lmin;
+    const int inside = (lo <= Lc) && (Lc <= hi);
+    const int shrinks = !(pb > pa);
+    if (gap) {
+        double scale = fabs(lo) > fabs(hi) ? fabs(lo) : fabs(hi);
+        if (fabs(Lc) > scale) scale = fabs(Lc);
+        if (scale < 1e-300) scale = 1e-300;
+        double g1 = fabs(Lc - lo) / scale, g2 = fabs(Lc - hi) / scale;
+        double ps = pa > pb ? pa : pb;
+        if (ps < 1e-300) ps = 1e-300;
+        double g3 = fabs(pa - pb) / ps;
+        double g = g1 < g2 ? g1 : g2;
+        *gap = g < g3 ? g : g3;
+    }
+    return inside && shrinks;
+}
+
+/* One server of Algorithm 3 over the explicit visit order idx[0..n).  w: start vector in, last
+ * accepted iterate out.  check = 0 switches the Check function off (every candidate is accepted:
+ * plain delay SGD).  *accepted receives J; *min_gap the closest any Check comparison came to a tie. */
+int oracle_delay_sgd_dense(const void *X, int xtype, int64_t m, int64_t d, const float *y,
+                           const int64_t *idx, int64_t n, double eta, double lambda, int loss,
+                           int tau, int check, double *w, int64_t *accepted, double *min_gap)
+{
+    if (!X || !y || !w || (n > 0 && !idx) || m < 1 || d < 1 || n < 0 || tau < 0 || tau > 1024) return ORACLE_BAD_ARG;
+    if (!(eta > 0.0) || lambda < 0.0 || !(eta * lambda < 1.0)) return ORACLE_BAD_ARG;
+    const int reach = tau > 1 ? tau : 1;             /* the second call needs w_{J-1} even at tau = 0 */
+    const int slots = reach + 2;                     /* w_{J-reach} .. w_J and the candidate */
+    double *hist = (double *)malloc(sizeof(double) * (size_t)slots * (size_t)d);
+    double *norm2 = (double *)malloc(sizeof(double) * (size_t)slots);
+    double *x = (double *)malloc(sizeof(double) * (size_t)d);
+    double *proj = (double *)malloc(sizeof(double) * (size_t)slots);
+    if (!hist || !norm2 || !x || !proj) { free(hist); free(norm2); free(x); free(proj); return ORACLE_NO_MEM; }
+#define ITER(t) (hist + (size_t)((t) % slots) * (size_t)d)
+    int64_t J = 0;
+    double n0 = 0.0;
+    for (int64_t c = 0; c < d; ++c) { ITER(0)[c] = w[c]; n0 += w[c] * w[c]; }
+    norm2[0] = n0;
+    double closest = INFINITY;
+    for (int64_t s = 0; s < n; ++s) {
+        const int64_t j = idx[s];
+        if (j < 0 || j >= m) { free(hist); free(norm2); free(x); free(proj); return ORACLE_BAD_ARG; }
+        double beta2 = 0.0;
+        for (int64_t c = 0; c < d; ++c) { x[c] = dense_at(X, xtype, d, j, c); beta2 += x[c] * x[c]; }
+        const int64_t at = J - tau > 0 ? J - tau : 0;            /* where the gradient was evaluated */
+        const double *wd = ITER(at), *wj = ITER(J);
+        double yhat = 0.0;
+        for (int64_t c = 0; c < d; ++c) yhat += wd[c] * x[c];
+        const double g = loss_slope(loss, (double)y[j], yhat);
+        double *cand = ITER(J + 1);
+        double Lc = 0.0, nc = 0.0;
+        for (int64_t c = 0; c < d; ++c) {
+            cand[c] = wj[c] - eta * lambda * wd[c] - eta * g * x[c];
+            Lc += cand[c] * x[c];
+            nc += cand[c] * cand[c];
+        }
+        int flag = 1;
+        if (check) {
+            const double rate = pow(eta * lambda + eta * beta2, 1.0 / (double)(tau > 1 ? tau : 1));
+            /* projections of the iterates the delayed gradient spans, w_{J-tau} .. w_J */
+            const int64_t first = J - reach > 0 ? J - reach : 0;
+            for (int64_t t = first; t <= J; ++t) {
+                double L = 0.0;
+                const double *wt = ITER(t);
+                for (int64_t c = 0; c < d; ++c) L += wt[c] * x[c];
+                proj[t % slots] = L;
+            }
+#define PERP2(t, L) (beta2 > 0.0 ? norm2[(t) % slots] - (L) * (L) / beta2 : norm2[(t) % slots])
+            for (int64_t t = first + 2; t <= J && flag; ++t) {
+                double gap;
+                const double La = proj[(t - 2) % slots], Lb = proj[(t - 1) % slots], Lt = proj[t % slots];
+                flag = oracle_check_triple(La, Lb, Lt, PERP2(t - 2, La), PERP2(t - 1, Lb), rate, &gap);
+                if (gap < closest) closest = gap;
+            }
+            if (flag && J >= 1) {
+                double gap;
+                const double La = proj[(J - 1) % slots], Lb = proj[J % slots];
+                flag = oracle_check_triple(La, Lb, Lc, PERP2(J - 1, La), PERP2(J, Lb), rate, &gap);
+                if (gap < closest) closest = gap;
+            }
+#undef PERP2
+        }
+        if (flag) {
+            ++J;
+            norm2[J % slots] = nc;
+        }
+    }
+    for (int64_t c = 0; c < d; ++c) w[c] = ITER(J)[c];
+#undef ITER
+    if (accepted) *accepted = J;
+    if (min_gap) *min_gap = closest;
+    free(hist); free(norm2); free(x); free(proj);
     return ORACLE_OK;
 }
 

@@ -588,3 +588,208 @@ def test_hinge_takes_zero_slope_exactly_at_the_kink():
     y = np.array([1.0], dtype=np.float32)
     w, closest = orc.sgd(orc.Dense(X), y, [0, 0, 0], 1.0, 0.0, orc.HINGE)
     assert w.tolist() == [1.0, 0.0] and closest == 0.0
+
+
+# ---------------------------------------------------------------- delay SGD with the Check function
+# (Section IV, Algorithms 3 and 4; the proof of Lemma 4 in the appendix)
+
+def _aligned_rows(rng, m, d, noise):
+    """Rows that nearly share one direction, so that projections on successive samples move the same
+    way and the Check function accepts more than the first update."""
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    X = np.outer(0.6 + 0.4 * rng.random(m), u) + noise * rng.standard_normal((m, d))
+    return X.astype(np.float32), np.ones(m, dtype=np.float32)
+
+
+@pytest.mark.parametrize("loss", [orc.HINGE, orc.LOGISTIC])
+def test_delay_zero_without_check_is_the_plain_chain(loss):
+    """With no delay the server's update is Eq. 5 on the newest iterate."""
+    rng = np.random.default_rng(21)
+    X = rng.standard_normal((50, 13)).astype(np.float32)
+    y = np.where(rng.random(50) < 0.5, 1.0, -1.0).astype(np.float32)
+    idx = orc.sample_indices(3, 1, 0, 300, 50)
+    w0 = rng.standard_normal(13)
+    want, _ = orc.sgd(orc.Dense(X), y, idx, 0.05, 0.02, loss, w0=w0)
+    got, accepted, _ = orc.delay_sgd(orc.Dense(X), y, idx, 0.05, 0.02, loss, 0, w0=w0, check=False)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+    assert accepted == 300
+
+
+def test_the_first_updates_of_a_delayed_server_all_see_the_start_vector():
+    """Until tau + 1 updates are done the gradient is evaluated at w_0 = 0, where the hinge slope is
+    -y and the regulariser vanishes: w_n = eta * sum of y_j x_j over the samples so far."""
+    rng = np.random.default_rng(22)
+    X = rng.standard_normal((20, 7)).astype(np.float32)
+    y = np.where(rng.random(20) < 0.5, 1.0, -1.0).astype(np.float32)
+    tau, eta = 5, 0.125
+    idx = [3, 17, 3, 8, 0, 11, 19]
+    for n in range(1, tau + 2):
+        w, accepted, _ = orc.delay_sgd(orc.Dense(X), y, idx[:n], eta, 0.3, orc.HINGE, tau, check=False)
+        want = eta * sum(float(y[j]) * X[j].astype(np.float64) for j in idx[:n])
+        np.testing.assert_allclose(w, want, rtol=1e-14, atol=1e-16)
+        assert accepted == n
+
+
+@pytest.mark.parametrize("loss", [orc.HINGE, orc.LOGISTIC])
+@pytest.mark.parametrize("tau", [1, 3])
+def test_one_row_over_and_over_follows_the_scalar_recurrences_in_the_proof_of_lemma_4(loss, tau):
+    """Proof of Lemma 4: along the sample, alpha_{n+1} = alpha_n - eta*lambda*alpha_{n-tau}
+    - eta*u(alpha_{n-tau})*beta^2; across it, the perpendicular part obeys
+    p_{n+1} = p_n - eta*lambda*p_{n-tau}.  The iterate is alpha*x/beta^2 + p."""
+    x = np.array([[0.5, -1.0, 0.25, 2.0]], dtype=np.float32)
+    yy = -1.0
+    xd = x[0].astype(np.float64)
+    beta2 = float(xd @ xd)
+    w0 = np.array([0.3, 0.1, -0.7, 0.2])
+    eta, lam, n = 0.03, 0.4, 40
+    alpha = [float(w0 @ xd)]
+    perp = [w0 - alpha[0] / beta2 * xd]
+    for t in range(n):
+        a_old, p_old = alpha[max(t - tau, 0)], perp[max(t - tau, 0)]
+        u = (-yy if yy * a_old < 1.0 else 0.0) if loss == orc.HINGE else -yy / (1.0 + math.exp(yy * a_old))
+        alpha.append(alpha[t] - eta * lam * a_old - eta * u * beta2)
+        perp.append(perp[t] - eta * lam * p_old)
+    w, accepted, _ = orc.delay_sgd(orc.Dense(x), np.array([yy], dtype=np.float32), [0] * n, eta, lam, loss, tau,
+                                   w0=w0, check=False)
+    np.testing.assert_allclose(w, alpha[n] / beta2 * xd + perp[n], rtol=1e-12, atol=1e-14)
+    assert accepted == n
+
+
+def test_check_function_on_hand_triples():
+    """Algorithm 4 on numbers worked by hand.  Length_min = (L_b - rate*L_a)/(1 - rate) is the point v
+    with (L_b - v)/(L_a - v) = rate; the new projection has to lie between L_b and it."""
+    # rising: L_a = 0, L_b = 1, rate 1/2 -> Length_min = 2, interval [1, 2]
+    for Lc, want in ((1.5, True), (1.0, True), (2.0, True), (2.5, False), (0.5, False)):
+        assert orc.check_triple(0.0, 1.0, Lc, 4.0, 3.0, 0.5)[0] is want
+    # falling: L_a = 4, L_b = 3, rate 1/2 -> Length_min = (3 - 2)/(1/2) = 2, interval [2, 3]
+    for Lc, want in ((2.5, True), (2.0, True), (3.0, True), (1.875, False), (3.25, False)):
+        assert orc.check_triple(4.0, 3.0, Lc, 1.0, 1.0, 0.5)[0] is want
+    # rate 1/4: L_a = -2, L_b = -1 -> Length_min = (-1 + 1/2)/(3/4) = -2/3
+    assert orc.check_triple(-2.0, -1.0, -0.75, 1.0, 0.5, 0.25)[0] is True
+    assert orc.check_triple(-2.0, -1.0, -0.625, 1.0, 0.5, 0.25)[0] is False
+    # the part across the sample must not grow from the older iterate to the newer one
+    assert orc.check_triple(0.0, 1.0, 1.5, 3.0, 3.0, 0.5)[0] is True
+    assert orc.check_triple(0.0, 1.0, 1.5, 3.0, 3.5, 0.5)[0] is False
+    # a contraction rate of 1 or more leaves no interval
+    assert orc.check_triple(0.0, 1.0, 1.5, 4.0, 3.0, 1.0)[0] is False
+    assert orc.check_triple(0.0, 1.0, 1.5, 4.0, 3.0, 1.5)[0] is False
+    # how close the decision was: (2 - 1.5)/2 against the interval, 1/4 against the perpendicular parts
+    assert orc.check_triple(0.0, 1.0, 1.5, 4.0, 3.0, 0.5)[1] == 0.25
+    assert orc.check_triple(0.0, 1.0, 1.9375, 4.0, 1.0, 0.5)[1] == 0.03125
+
+
+def test_delay_server_hand_case():
+    """x = (1, 0), y = +1, hinge, w_0 = (0, 1), tau = 1, every sample the same row; exact binary
+    fractions throughout.  beta^2 = 1, so rate = eta*lambda + eta.
+
+    eta = 1/2, lambda = 1/4 (rate 5/8):
+      w_1 = w_0 - w_0/8 + x/2 = (1/2, 7/8), accepted (no triple yet).
+      w_2: gradient at w_0 (margin 0): w_1 - w_0/8 + x/2 = (1, 3/4).  Triple projections 0, 1/2, 1;
+           Length_min = (1/2)/(3/8) = 4/3, 1 lies in [1/2, 4/3]; perpendicular parts 1 -> 7/8.  Accepted.
+      w_3: gradient at w_1 (margin 1/2): w_2 - w_1/8 + x/2 = (23/16, 41/64).  Projections 1/2, 1, 23/16;
+           Length_min = (1 - 5/16)/(3/8) = 11/6; inside.  Accepted.
+      w_4: gradient at w_2 (margin 1, slope 0): w_3 - w_2/8 = (21/16, 35/64).  Projections 1, 23/16, 21/16;
+           the interval is [23/16, 13/6] and 21/16 is below it: rejected, and so is every later sample,
+           because a rejected candidate leaves the server as it was.
+    eta = 1/4, lambda = 1/2 (rate 3/8):
+      w_1 = (1/4, 7/8); w_2 candidate (1/2, 3/4): Length_min = (1/4)/(5/8) = 2/5 < 1/2: rejected for good."""
+    X = np.array([[1.0, 0.0]], dtype=np.float32)
+    y = np.array([1.0], dtype=np.float32)
+    want = {1: [0.5, 0.875], 2: [1.0, 0.75], 3: [1.4375, 0.640625]}
+    for n in (1, 2, 3, 4, 9):
+        w, accepted, _ = orc.delay_sgd(orc.Dense(X), y, [0] * n, 0.5, 0.25, orc.HINGE, 1, w0=[0.0, 1.0])
+        assert accepted == min(n, 3) and w.tolist() == want[min(n, 3)]
+    for n in (1, 2, 7):
+        w, accepted, _ = orc.delay_sgd(orc.Dense(X), y, [0] * n, 0.25, 0.5, orc.HINGE, 1, w0=[0.0, 1.0])
+        assert accepted == 1 and w.tolist() == [0.25, 0.875]
+    # without the Check function nothing is thrown away
+    w, accepted, _ = orc.delay_sgd(orc.Dense(X), y, [0] * 4, 0.5, 0.25, orc.HINGE, 1, w0=[0.0, 1.0], check=False)
+    assert accepted == 4 and w.tolist() == [1.3125, 0.546875]
+
+
+def test_first_call_of_check_looks_at_the_older_iterates_along_the_new_sample():
+    """Rows a = (1, 0) and b = (0, 1), hinge, start 0, eta = 1/2, lambda = 1/4, tau = 2 (rate sqrt(5/8)).
+    Two visits of a give w_1 = (1/2, 0), w_2 = (1, 0): the second passes because 1 lies between 1/2 and
+    (1/2)/(1 - rate) > 2 and nothing is perpendicular to a.  Then b arrives.  Along b the three iterates
+    w_0, w_1, w_2 all project to 0 while the part across b grew from 0 to 1/2: the first call rejects,
+    before any candidate is formed.  With tau = 1 that call has only two iterates to look at and the
+    sample is lost at the second call instead: projections 0, 0 leave the single point 0 and the
+    candidate (15/16, 1/2) projects to 1/2."""
+    X = np.array([[1.0, 0.0], [0.0, 1.0]], dtype=np.float32)
+    y = np.array([1.0, 1.0], dtype=np.float32)
+    for tau in (2, 1):
+        w, accepted, _ = orc.delay_sgd(orc.Dense(X), y, [0, 0, 1, 1, 1], 0.5, 0.25, orc.HINGE, tau)
+        assert accepted == 2 and w.tolist() == [1.0, 0.0]
+
+
+def _brute_force_delay_server(X, y, idx, eta, lam, loss, tau, w0):
+    """Algorithms 3 and 4 with every iterate kept and the perpendicular parts formed as vectors."""
+    hist, taken = [np.array(w0, dtype=np.float64)], []
+    for j in idx:
+        x, yy = X[j].astype(np.float64), float(y[j])
+        J = len(hist) - 1
+        old = hist[max(J - tau, 0)]
+        yhat = float(old @ x)
+        slope = (-yy if yy * yhat < 1.0 else 0.0) if loss == orc.HINGE else -yy / (1.0 + math.exp(yy * yhat))
+        cand = hist[J] - eta * lam * old - eta * slope * x
+        beta2 = float(x @ x)
+        rate = (eta * lam + eta * beta2) ** (1.0 / max(tau, 1))
+
+        def passes(a, b, c):
+            if rate >= 1.0:
+                return False
+            La, Lb, Lc = float(a @ x), float(b @ x), float(c @ x)
+            Lmin = (Lb - rate * La) / (1.0 - rate)
+            across_a, across_b = a - La / beta2 * x, b - Lb / beta2 * x
+            return min(Lmin, Lb) <= Lc <= max(Lmin, Lb) and not np.linalg.norm(across_b) > np.linalg.norm(across_a)
+
+        window = hist[max(J - tau, 0):]
+        ok = all(passes(*window[i:i + 3]) for i in range(len(window) - 2))
+        if ok and J >= 1:
+            ok = passes(hist[J - 1], hist[J], cand)
+        taken.append(ok)
+        if ok:
+            hist.append(cand)
+    return hist[-1], taken
+
+
+@pytest.mark.parametrize("loss", [orc.HINGE, orc.LOGISTIC])
+@pytest.mark.parametrize("tau", [0, 1, 2, 4])
+def test_delay_server_against_brute_force(loss, tau):
+    rng = np.random.default_rng(100 + tau)
+    X, y = _aligned_rows(rng, 96, 12, 1e-2)
+    seen = 0
+    for eta, lam in ((0.5, 0.25), (0.9, 0.05), (0.25, 0.5)):
+        for trial in range(4):
+            w0 = 0.5 * rng.standard_normal(12)
+            idx = orc.sample_indices(7 + trial, tau, 0, 300, 96)
+            w, accepted, closest = orc.delay_sgd(orc.Dense(X), y, idx, eta, lam, loss, tau, w0=w0)
+            if closest < 1e-9:
+                continue                                     # a tie that rounding may break either way
+            want, taken = _brute_force_delay_server(X, y, idx, eta, lam, loss, tau, w0)
+            assert accepted == sum(taken)
+            np.testing.assert_allclose(w, want, rtol=1e-11, atol=1e-13)
+            # rejected samples leave no trace: the same server without Check, fed only the samples
+            # that were taken, walks through the same iterates
+            kept = [j for j, ok in zip(idx, taken) if ok]
+            again, n_again, _ = orc.delay_sgd(orc.Dense(X), y, kept, eta, lam, loss, tau, w0=w0, check=False)
+            assert n_again == accepted and again.tolist() == w.tolist()
+            seen = max(seen, accepted)
+    assert seen >= 5                                          # the cases do get past the first updates
+
+
+def test_delay_servers_take_their_own_streams_and_phase_2_weights_by_accepted_updates():
+    """Algorithm 3, phase 2: v = sum_i weight_i w_i with the weights of Eq. 8 on the number of updates
+    each server has made."""
+    rng = np.random.default_rng(31)
+    X, y = _aligned_rows(rng, 64, 9, 1e-2)
+    n = [40, 25, 0, 33]
+    W, accepted, _ = orc.run_delay_chains(orc.Dense(X), y, n, 0.5, 0.25, orc.LOGISTIC, 12, 2, check=False)
+    assert accepted.tolist() == n and not W[2].any()
+    for i in (0, 1, 3):
+        w, _, _ = orc.delay_sgd(orc.Dense(X), y, orc.sample_indices(12, i, 0, n[i], 64), 0.5, 0.25, orc.LOGISTIC, 2,
+                                check=False)
+        assert W[i].tolist() == w.tolist()
+    a = orc.weights_rate(accepted, 1 - 0.5 * 0.25)
+    np.testing.assert_allclose(orc.combine(W, a), sum(a[i] * W[i] for i in range(4)), rtol=1e-15)
