@@ -53,13 +53,98 @@ def measured_traffic(workload: str):
     return rec.get("hbm_bytes_per_launch")
 
 
+def bench_delay_servers(args, torch, api, wl) -> int:
+    """The servers of Section IV (Algorithm 3): one step is phase 1 (wpsgd_run_delay_chains: every server
+    consumes its samples, under the Check function of Algorithm 4 unless --no-check) and phase 2 (the
+    weights of Eq. 8 on the servers' accepted updates, wpsgd_weights_rate, and wpsgd_combine).  The
+    metric counts samples consumed; a sample's algorithmic traffic is its row and its label."""
+    t_gen = time.time()
+    w = wl.delay_servers()
+    t_gen = time.time() - t_gen
+    tau, check = int(w.meta["tau"]), not args.no_check
+    X = api.matrix_from_workload(w)
+    y = torch.from_numpy(w.y).cuda()
+    k, d = w.k, w.d
+    w_start = torch.from_numpy(w.meta["w_start"]).cuda()
+    W = torch.empty((k, d), dtype=torch.float32, device="cuda")
+    accepted = torch.empty(k, dtype=torch.int64, device="cuda")
+    v = torch.empty(d, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(256, api.wpsgd_run_delay_chains_workspace(X, k, tau)), dtype=torch.uint8, device="cuda")
+    ws_comb = torch.empty(max(256, api.wpsgd_combine_workspace(k, d)), dtype=torch.uint8, device="cuda")
+    rate = 1.0 - w.eta * w.lam
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record()
+        api.wpsgd_run_delay_chains(X, y, w.n_steps, w.eta, w.lam, w.loss, w.seed, tau, check=check, w_start=w_start,
+                                   W=W, accepted=accepted, workspace=ws)
+        if ev is not None:
+            ev[1].record()
+        a = api.wpsgd_weights_rate(accepted.cpu().numpy(), rate)
+        api.wpsgd_combine(W, a, w_out=v, workspace=ws_comb)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    samples = int(w.n_steps.sum())
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    bytes_per_sample = w.row_bytes() + 4
+    achieved = bytes_per_sample * samples / (kernel_ms * 1e-3) / 1e9
+    acc = accepted.cpu().numpy()
+    out = {
+        "metric": "samples/sec consumed by delay-SGD servers (all servers)",
+        "value": samples / (ms_per_step * 1e-3),
+        "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "delay_servers", "m": w.m, "d": d, "k": k, "tau": tau, "check": check,
+                   "samples_per_step": samples, "storage": "f32",
+                   "loss": "hinge" if w.loss == wl.HINGE else "logistic",
+                   "accepted_updates_min_mean_max": [int(acc.min()), float(acc.mean()), int(acc.max())]},
+        "roofline": {"bound": "hbm", "kernel": "delay_server_kernel (wpsgd_run_delay_chains)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_sample": bytes_per_sample, "kernel_ms": kernel_ms,
+                     "most_samples_one_server": int(w.n_steps.max()),
+                     "us_per_sample_busiest_server": kernel_ms * 1e3 / max(1, int(w.n_steps.max()))},
+        "data_generation_s": t_gen,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        servers = min(k, 32)
+        tc = time.perf_counter()
+        Wo = np.zeros((servers, d))
+        acc_o = np.zeros(servers, dtype=np.int64)
+        for i in range(servers):
+            idx = orc.sample_indices(w.seed, i, 0, int(w.n_steps[i]), w.m)
+            Wo[i], acc_o[i], _ = orc.delay_sgd(orc.Dense(w.dense), w.y, idx, w.eta, w.lam, w.loss, tau,
+                                               w0=w.meta["w_start"].astype(np.float64), check=check)
+        tc = time.perf_counter() - tc
+        out["cpu_baseline"] = {"value": float(w.n_steps[:servers].sum()) / tc, "unit": "samples/s", "cores": 1,
+                               "kind": "oracle", "sample": f"the first {servers} servers in full", "seconds": tc}
+        Wg = W[:servers].cpu().numpy().astype(np.float64)
+        out["parity_rel_l2"] = float(np.linalg.norm(Wg - Wo) / max(np.linalg.norm(Wo), 1e-300))
+        out["parity_accepted_equal"] = bool(np.array_equal(acc[:servers], acc_o))
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="dense_logistic",
-                    choices=["tiny_hinge", "dense_logistic", "sparse_hinge", "many_chains", "wide_bf16"])
+                    choices=["tiny_hinge", "dense_logistic", "sparse_hinge", "many_chains", "wide_bf16",
+                             "delay_servers"])
+    ap.add_argument("--no-check", action="store_true",
+                    help="delay_servers: plain delay SGD, every candidate kept (default: under the Check function)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--block-steps", type=int, default=0)
@@ -98,6 +183,9 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"calibration_copy_bytes_per_dispatch": n * 4, "dispatches": 3}))
         return 0
+
+    if args.workload == "delay_servers":
+        return bench_delay_servers(args, torch, api, wl)
 
     t_gen = time.time()
     w = wl.FULL[args.workload]()

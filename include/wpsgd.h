@@ -153,6 +153,37 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
  * for each other (their rows of W, and whatever was computed from them, are NaN), or an error.   */
 int wpsgd_chains_status(const void *workspace, void *stream);
 
+/* ---- delay SGD under the Check function (Section IV, Algorithm 3 phase 1, Algorithm 4; Lemma 4) ----
+ * Server i (i = 0..k-1) receives n_samples[i] samples, the rows its own sample stream names (see
+ * wpsgd_sample_indices), and keeps the iterates w_0, w_1, .. w_J it has accepted.  For a sample (x, y)
+ * the gradient was taken tau iterates ago:
+ *     candidate = w_J - eta*lambda*w_{J-tau} - eta * dL/dyhat(y, w_{J-tau}.x) * x
+ * (an index below 0 means w_0).  With check != 0 the candidate becomes w_{J+1} only if Algorithm 4
+ * accepts, first, every triple of consecutive iterates among w_{J-tau} .. w_J and then the triple
+ * (w_{J-1}, w_J, candidate), all measured along x: with L_w = w.x, beta^2 = x.x,
+ *     rate = (eta*lambda + eta*beta^2)^(1/max(tau,1))      (c* = 1 bounds the slope of both losses)
+ *     Length_min = (L_b - rate*L_a) / (1 - rate)
+ * a triple (a, b, c) passes if rate < 1, L_c lies between L_b and Length_min (ends included) and
+ * |b|^2 - L_b^2/beta^2 <= |a|^2 - L_a^2/beta^2 (the part across the sample does not grow, as the proof
+ * of Lemma 4 requires).  Triples that would reach before w_0 are not tested.  A rejected candidate is
+ * dropped, its sample is spent, and the server is as it was.  With check == 0 every candidate is kept:
+ * plain delay SGD.  All arithmetic is fp64.
+ *   X            DEVICE, dense rows only (CSR: UNSUPPORTED)
+ *   n_samples    HOST, k entries >= 0
+ *   tau          delay, 0 <= tau <= 16 (more: UNSUPPORTED)
+ *   w_start      DEVICE, d entries fp32: w_0 of every server; NULL means zero (Algorithm 3)
+ *   W            DEVICE out, k x d row-major fp32: the last accepted iterate of each server
+ *   accepted     DEVICE out, k entries: J of each server.  Phase 2 of Algorithm 3 is wpsgd_weights_rate
+ *                on these counts followed by wpsgd_combine.
+ *   workspace    DEVICE scratch of at least wpsgd_run_delay_chains_workspace(X, k, tau) bytes (0 is
+ *                returned for arguments the call would refuse), 256-byte aligned
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.                              */
+size_t wpsgd_run_delay_chains_workspace(const wpsgd_matrix *X, int k, int tau);
+int wpsgd_run_delay_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_samples,
+                           double eta, double lambda, wpsgd_loss loss, uint64_t seed, int tau, int check,
+                           const float *w_start, float *W, int64_t *accepted,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- weights (Eq. 6; Eq. 8 for a chosen contraction rate r) ----
  *   a[i] = rate^{T_i} / sum_j rate^{T_j},  T_i = max_j n_steps[j] - n_steps[i],
  *   rate = 1 - eta*lambda (wpsgd_weights) or r in (0, 1] (wpsgd_weights_rate).

@@ -29,7 +29,7 @@ EXPORTS = [
     "wpsgd_stream_rows", "wpsgd_objective_workspace", "wpsgd_objective",
     "wpsgd_run_chains_from", "wpsgd_shard_indices", "wpsgd_shard_indices_device",
     "wpsgd_run_spans_workspace", "wpsgd_run_spans", "wpsgd_span_condition", "wpsgd_objective_static",
-    "wpsgd_chains_status",
+    "wpsgd_chains_status", "wpsgd_run_delay_chains_workspace", "wpsgd_run_delay_chains",
 ]
 
 
@@ -74,6 +74,9 @@ def load():
     L.wpsgd_run_chains.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, vp, vp, sz, pp, vp]
     L.wpsgd_run_chains_from.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, ci, vp, vp, vp, vp, sz, pp, vp]
     L.wpsgd_chains_status.argtypes = [vp, vp]
+    L.wpsgd_run_delay_chains_workspace.argtypes = [pm, ci, ci]
+    L.wpsgd_run_delay_chains_workspace.restype = sz
+    L.wpsgd_run_delay_chains.argtypes = [pm, vp, ci, vp, f64, f64, ci, u64, ci, ci, vp, vp, vp, vp, sz, vp]
     L.wpsgd_run_spans_workspace.argtypes = [pm, ci, ci, pp]
     L.wpsgd_run_spans_workspace.restype = sz
     L.wpsgd_run_spans.argtypes = [pm, vp, ci, vp, i64, f64, f64, ci, u64, ci, vp, vp, vp, sz, pp, vp]
@@ -257,6 +260,42 @@ def wpsgd_run_chains_from(X: Matrix, y: torch.Tensor, n_steps, eta, lam, loss, s
     if rc != OK:
         raise WpsgdError(rc, "wpsgd_run_chains_from")
     return W
+
+
+def wpsgd_run_delay_chains_workspace(X: Matrix, k, tau) -> int:
+    cm = X.c_struct()
+    return int(load().wpsgd_run_delay_chains_workspace(ctypes.byref(cm), int(k), int(tau)))
+
+
+def wpsgd_run_delay_chains(X: Matrix, y: torch.Tensor, n_samples, eta, lam, loss, seed, tau, check=True,
+                           w_start: Optional[torch.Tensor] = None, W: Optional[torch.Tensor] = None,
+                           accepted: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           stream=None):
+    """Phase 1 of delay SGD under the Check function: k servers, server i fed n_samples[i] samples.
+    Returns (W, accepted): k x d float32 and k int64, both on the GPU."""
+    n = _steps(n_samples)
+    k = int(n.size)
+    dev = y.device
+    assert y.is_cuda and y.dtype == torch.float32 and y.numel() == X.m
+    if w_start is not None:
+        assert w_start.is_cuda and w_start.dtype == torch.float32 and w_start.is_contiguous() and w_start.numel() == X.d
+    if W is None:
+        W = torch.empty((k, X.d), dtype=torch.float32, device=dev)
+    if accepted is None:
+        accepted = torch.empty(k, dtype=torch.int64, device=dev)
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.shape == (k, X.d)
+    assert accepted.is_cuda and accepted.dtype == torch.int64 and accepted.is_contiguous() and accepted.numel() == k
+    cm = X.c_struct()
+    if workspace is None:
+        need = load().wpsgd_run_delay_chains_workspace(ctypes.byref(cm), k, int(tau))
+        workspace = _workspace(max(int(need), 256), dev, stream)
+    rc = load().wpsgd_run_delay_chains(ctypes.byref(cm), y.data_ptr(), k, n.ctypes.data, float(eta), float(lam),
+                                       int(loss), int(seed), int(tau), int(bool(check)),
+                                       w_start.data_ptr() if w_start is not None else None, W.data_ptr(),
+                                       accepted.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if rc != OK:
+        raise WpsgdError(rc, "wpsgd_run_delay_chains")
+    return W, accepted
 
 
 def wpsgd_run_spans_workspace(X: Matrix, k, loss, plan=None) -> int:

@@ -34,6 +34,7 @@ UNITS = [
     ("combine", "combine.hip", []),
     ("objective", "objective.hip", []),
     ("chain_dense_mem", "chain_dense_mem.hip", []),
+    ("chain_delay", "chain_delay.hip", []),
     ("chain_csr", "chain_csr.hip", []),
     ("chain_csr_pair", "chain_csr_pair.hip", []),
     ("chain_dense_reg_f32_hinge", "chain_dense_reg.hip", ["-DWPSGD_TX_BF16=0", "-DWPSGD_LOSS=0"]),

@@ -577,6 +577,61 @@ int wpsgd_run_chains_from(const wpsgd_matrix *X, const float *y, int k, const in
                            workspace_bytes, plan, stream, false);
 }
 
+static size_t delay_ring_bytes(const wpsgd_matrix *X, int k, int tau)
+{
+    return (size_t)k * (size_t)(std::max(tau, 1) + 2) * (size_t)X->d * sizeof(double);
+}
+
+size_t wpsgd_run_delay_chains_workspace(const wpsgd_matrix *X, int k, int tau)
+{
+    if (check_matrix(X) != WPSGD_OK || !X->dense || k < 1 || tau < 0 || tau > kDelayMaxTau) return 0;
+    return align256((size_t)k * sizeof(int64_t)) + align256(delay_ring_bytes(X, k, tau));
+}
+
+int wpsgd_run_delay_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_samples,
+                           double eta, double lambda, wpsgd_loss loss, uint64_t seed, int tau, int check,
+                           const float *w_start, float *W, int64_t *accepted,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_matrix(X);
+    if (rc != WPSGD_OK) return rc;
+    if (!y || !W || !accepted || tau < 0) return WPSGD_INVALID_ARG;
+    rc = check_steps(k, n_samples);
+    if (rc != WPSGD_OK) return rc;
+    if (!(eta > 0.0) || !(lambda >= 0.0) || !(eta * lambda < 1.0)) return WPSGD_INVALID_ARG;
+    if (loss != WPSGD_HINGE && loss != WPSGD_LOGISTIC) return WPSGD_INVALID_ARG;
+    if (!X->dense || tau > kDelayMaxTau) return WPSGD_UNSUPPORTED;
+    if (!workspace || ((uintptr_t)workspace % 256) != 0) return WPSGD_INVALID_ARG;
+    if (workspace_bytes < wpsgd_run_delay_chains_workspace(X, k, tau)) return WPSGD_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(workspace);
+    rc = upload(base, n_samples, (size_t)k * sizeof(int64_t), s);
+    if (rc != WPSGD_OK) return rc;
+    DelayArgs a{};
+    a.dense = X->dense;
+    a.ld = X->ld;
+    a.y = y;
+    a.m = X->m;
+    a.d = X->d;
+    a.k = k;
+    a.n_samples = reinterpret_cast<const int64_t *>(base);
+    a.w_start = w_start;
+    a.eta = eta;
+    a.lambda = lambda;
+    a.loss = (int)loss;
+    a.tau = tau;
+    a.check = check != 0;
+    a.seed_lo = (uint32_t)seed;
+    a.seed_hi = (uint32_t)(seed >> 32);
+    a.ring = reinterpret_cast<double *>(base + align256((size_t)k * sizeof(int64_t)));
+    a.W = W;
+    a.accepted = accepted;
+    const bool start_ok = !w_start || (uintptr_t)w_start % 4 == 0;
+    if (!start_ok) return WPSGD_INVALID_ARG;
+    hipError_t e = launch_delay_servers(a, (int)X->dtype, dense_vec(X), s);
+    return e == hipSuccess ? WPSGD_OK : hip_fail(e);
+}
+
 int wpsgd_chains_status(const void *workspace, void *stream)
 {
     if (!workspace) return WPSGD_INVALID_ARG;

@@ -1,0 +1,242 @@
+// Delay SGD under the Check function (Section IV, Algorithms 3 and 4; Lemma 4): one workgroup is one
+// server.  It keeps the accepted iterates w_{J-reach} .. w_J (reach = max(tau, 1)) and room for one
+// candidate as a ring of fp64 vectors in the workspace.  Every thread owns the same columns of every
+// vector in every pass, so the ring needs no synchronisation of its own; it is re-read every sample
+// and stays in the cache of the compute unit's XCD.
+//
+// Per sample x (one row of the data set), one pass over the row forms beta^2 = x.x and the projections
+// L_t = w_t.x of the iterates the delayed gradient spans.  From those scalars alone every thread takes
+// the same decision: the slope u at w_{J-tau}, the triples of the first call of Check, and the triple
+// (w_{J-1}, w_J, candidate) of the second call, whose third projection follows from the update rule,
+//     L_c = L_J - eta*lambda*L_{J-tau} - eta*u*beta^2,
+// so a sample that is thrown away costs no second pass.  Only an accepted candidate is written:
+//     w_{J+1} = w_J - eta*lambda*w_{J-tau} - eta*u*x          (the recurrence in the proof of Lemma 4)
+// together with its squared length, which later tests need for the part across a sample,
+// |w|^2 - L^2/beta^2.  All arithmetic is fp64; the result is rounded to fp32 once, at the end.
+#include "device_utils.h"
+#include "internal.h"
+
+namespace wpsgd {
+namespace {
+
+constexpr int kDelayThreads = 256;
+constexpr int kDelayWaves = kDelayThreads / kWave;
+
+template <typename TX, int VEC> struct DelayRow;
+template <> struct DelayRow<float, 1> {
+    double x[1];
+    __device__ void load(const float *p) { x[0] = (double)p[0]; }
+};
+template <> struct DelayRow<float, 4> {
+    double x[4];
+    __device__ void load(const float *p)
+    {
+        const float4 q = *reinterpret_cast<const float4 *>(p);
+        x[0] = (double)q.x; x[1] = (double)q.y; x[2] = (double)q.z; x[3] = (double)q.w;
+    }
+};
+template <> struct DelayRow<uint16_t, 1> {
+    double x[1];
+    __device__ void load(const uint16_t *p) { x[0] = (double)bf16_one(p[0]); }
+};
+template <> struct DelayRow<uint16_t, 8> {
+    double x[8];
+    __device__ void load(const uint16_t *p)
+    {
+        const uint4 q = *reinterpret_cast<const uint4 *>(p);
+        x[0] = (double)bf16_lo(q.x); x[1] = (double)bf16_hi(q.x); x[2] = (double)bf16_lo(q.y); x[3] = (double)bf16_hi(q.y);
+        x[4] = (double)bf16_lo(q.z); x[5] = (double)bf16_hi(q.z); x[6] = (double)bf16_lo(q.w); x[7] = (double)bf16_hi(q.w);
+    }
+};
+
+// One triple of Algorithm 4: the newest projection must lie between the middle one and
+// Length_min = (L_b - rate*L_a)/(1 - rate), ends included, and the part of the middle iterate across
+// the sample (squared length pb) must not be longer than that of the oldest (pa).
+__device__ inline bool check_triple(double La, double Lb, double Lc, double pa, double pb, double rate)
+{
+    if (!(rate < 1.0)) return false;
+    const double Lmin = (Lb - rate * La) / (1.0 - rate);
+    const double lo = Lmin < Lb ? Lmin : Lb, hi = Lmin < Lb ? Lb : Lmin;
+    return lo <= Lc && Lc <= hi && !(pb > pa);
+}
+
+// MAXW: how many iterates one pass can project (reach + 1 are needed).
+template <typename TX, int VEC, int MAXW>
+__global__ __launch_bounds__(kDelayThreads) void delay_server_kernel(DelayArgs a)
+{
+    constexpr int NT = kDelayThreads, NW = kDelayWaves;
+    __shared__ double red[2][NW][MAXW + 1];
+    __shared__ double nrm[MAXW + 1];               // squared lengths of the ring's vectors, by slot
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int chain = blockIdx.x;
+    const int64_t n = a.n_samples[chain];
+    const int64_t d = a.d;
+    const int reach = a.tau > 1 ? a.tau : 1;
+    const int slots = reach + 2;
+    const TX *X = static_cast<const TX *>(a.dense);
+    double *ring = a.ring + (int64_t)chain * slots * d;
+    const double eta = a.eta, eta_lambda = a.eta * a.lambda;
+    int parity = 0;
+
+    // sums `count` values per thread over the workgroup; every thread receives the same totals
+    auto block_sums = [&](double(&v)[MAXW + 1], int count) {
+#pragma unroll
+        for (int t = 0; t <= MAXW; ++t)
+            if (t < count) {
+                const double w = wave_sum_lane63(v[t]);
+                if (lane == kWave - 1) red[parity][wave][t] = w;
+            }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t <= MAXW; ++t)
+            if (t < count) {
+                double sum = red[parity][0][t];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) sum += red[parity][w][t];
+                v[t] = sum;
+            }
+        parity ^= 1;
+    };
+
+    {   // w_0 and its squared length
+        double v[MAXW + 1];
+        v[0] = 0.0;
+        for (int64_t col = (int64_t)tid * VEC; col < d; col += (int64_t)NT * VEC)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const double w = a.w_start ? (double)a.w_start[col + j] : 0.0;
+                ring[col + j] = w;
+                v[0] += w * w;
+            }
+        block_sums(v, 1);
+        if (tid == 0) nrm[0] = v[0];
+    }
+
+    RowWindow win;
+    win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
+    int64_t J = 0;                                  // accepted updates so far
+
+    for (int64_t s = 0; s < n; ++s) {
+        const uint32_t row = win.get(s);
+        const TX *xr = X + (int64_t)row * a.ld;
+        const double y = (double)a.y[row];
+        const int64_t at = J - a.tau > 0 ? J - a.tau : 0;          // where the gradient is evaluated
+        // iterates to project: w_{J-reach} .. w_J under Check, w_{J-tau} alone without it
+        const int64_t first = a.check ? (J - reach > 0 ? J - reach : 0) : at;
+        const int nwin = a.check ? (int)(J - first) + 1 : 1;
+        int64_t off[MAXW];
+#pragma unroll
+        for (int t = 0; t < MAXW; ++t) off[t] = (int64_t)((first + t) % slots) * d;
+
+        double v[MAXW + 1];                          // v[t] = w_{first+t}.x, v[MAXW] = x.x
+#pragma unroll
+        for (int t = 0; t <= MAXW; ++t) v[t] = 0.0;
+        for (int64_t col = (int64_t)tid * VEC; col < d; col += (int64_t)NT * VEC) {
+            DelayRow<TX, VEC> c;
+            c.load(xr + col);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) v[MAXW] += c.x[j] * c.x[j];
+#pragma unroll
+            for (int t = 0; t < MAXW; ++t)
+                if (t < nwin) {
+                    const double *w = ring + off[t] + col;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) v[t] += w[j] * c.x[j];
+                }
+        }
+        // the totals are wanted in v[0..nwin) and v[MAXW]; move x.x next to the projections
+        {
+            const double b = v[MAXW];
+#pragma unroll
+            for (int t = 0; t < MAXW; ++t)
+                if (t == nwin) v[t] = b;
+            if (nwin == MAXW) v[MAXW] = b;
+        }
+        block_sums(v, nwin + 1);
+        double beta2 = v[MAXW], L_new = 0.0, L_prev = 0.0;
+#pragma unroll
+        for (int t = 0; t < MAXW; ++t) {
+            if (t == nwin) beta2 = v[t];
+            if (t == nwin - 1) L_new = v[t];             // w_J.x (without Check: w_{J-tau}.x)
+            if (t == nwin - 2) L_prev = v[t];            // w_{J-1}.x
+        }
+        const double yhat = (a.check && a.tau == 0) ? L_new : v[0];
+        const double g = a.loss == kLossHinge ? loss_slope<kLossHinge>(y, yhat) : loss_slope<kLossLogistic>(y, yhat);
+
+        bool keep = true;
+        if (a.check) {
+            const double base = eta_lambda + eta * beta2;
+            const double rate = reach == 1 ? base : pow(base, 1.0 / (double)reach);
+            auto across2 = [&](int64_t t, double L) {
+                const double n2 = nrm[t % slots];
+                return beta2 > 0.0 ? n2 - L * L / beta2 : n2;
+            };
+#pragma unroll
+            for (int t = 2; t < MAXW; ++t)
+                if (t < nwin && keep)
+                    keep = check_triple(v[t - 2], v[t - 1], v[t], across2(first + t - 2, v[t - 2]),
+                                        across2(first + t - 1, v[t - 1]), rate);
+            if (keep && J >= 1) {
+                const double L_cand = L_new - eta_lambda * yhat - eta * g * beta2;
+                keep = check_triple(L_prev, L_new, L_cand, across2(J - 1, L_prev), across2(J, L_new), rate);
+            }
+        }
+        if (keep) {
+            const double *wj = ring + (int64_t)(J % slots) * d;
+            const double *wd = ring + (int64_t)(at % slots) * d;
+            double *dst = ring + (int64_t)((J + 1) % slots) * d;
+            const double eg = eta * g;
+            double u[MAXW + 1];
+            u[0] = 0.0;
+            for (int64_t col = (int64_t)tid * VEC; col < d; col += (int64_t)NT * VEC) {
+                DelayRow<TX, VEC> c;
+                c.load(xr + col);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    const double w = wj[col + j] - eta_lambda * wd[col + j] - eg * c.x[j];
+                    dst[col + j] = w;
+                    u[0] += w * w;
+                }
+            }
+            block_sums(u, 1);
+            ++J;
+            if (tid == 0) nrm[J % slots] = u[0];
+        }
+    }
+
+    const double *last = ring + (int64_t)(J % slots) * d;
+    float *out = a.W + (int64_t)chain * d;
+    for (int64_t col = (int64_t)tid * VEC; col < d; col += (int64_t)NT * VEC)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) out[col + j] = (float)last[col + j];
+    if (tid == 0) a.accepted[chain] = J;
+}
+
+template <typename TX, int VEC>
+hipError_t launch_reach(const DelayArgs &a, hipStream_t s)
+{
+    const int need = (a.tau > 1 ? a.tau : 1) + 1;
+#define WPSGD_DELAY_TRY(MAXW)                                                                                   \
+    if (need <= MAXW) {                                                                                         \
+        hipLaunchKernelGGL((delay_server_kernel<TX, VEC, MAXW>), dim3(a.k), dim3(kDelayThreads), 0, s, a);      \
+        return hipGetLastError();                                                                               \
+    }
+    WPSGD_DELAY_TRY(3)
+    WPSGD_DELAY_TRY(5)
+    WPSGD_DELAY_TRY(kDelayMaxTau + 1)
+#undef WPSGD_DELAY_TRY
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_delay_servers(const DelayArgs &a, int dtype, int vec, hipStream_t s)
+{
+    if (dtype == WPSGD_BF16) return vec > 1 ? launch_reach<uint16_t, 8>(a, s) : launch_reach<uint16_t, 1>(a, s);
+    return vec > 1 ? launch_reach<float, 4>(a, s) : launch_reach<float, 1>(a, s);
+}
+
+}  // namespace wpsgd

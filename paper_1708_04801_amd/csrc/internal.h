@@ -53,6 +53,24 @@ struct ChainArgs {
     void *state;              // k x d model vectors in HBM (state_in_hbm plans), else unused
 };
 
+// Arguments of the delay-SGD servers (Section IV, Algorithms 3 and 4): workgroup i is server i.
+constexpr int kDelayMaxTau = 16;
+struct DelayArgs {
+    const void *dense;        // row-major, ld elements per row (fp32 or bfloat16 bits)
+    int64_t ld;
+    const float *y;
+    int64_t m, d;
+    int k;
+    const int64_t *n_samples; // DEVICE, k entries: samples server i receives
+    const float *w_start;     // DEVICE, d entries, or NULL for zero
+    double eta, lambda;
+    int loss, tau, check;
+    uint32_t seed_lo, seed_hi;
+    double *ring;             // DEVICE, k x (max(tau,1)+2) x d: the iterates each server keeps
+    float *W;                 // k x d out
+    int64_t *accepted;        // k out: updates each server has made
+};
+
 enum class Family { DenseReg, DenseMem, Csr };
 
 // A fully resolved plan (every field chosen).
@@ -77,6 +95,7 @@ hipError_t launch_csr(const Plan &p, const ChainArgs &a, hipStream_t s);
 hipError_t launch_csr_pair(const Plan &p, const ChainArgs &a, hipStream_t s);   // two waves per chain
 bool dense_reg_has(const Plan &p);   // is (dtype, loss, threads, ept, vec, B, P) instantiated?
 
+hipError_t launch_delay_servers(const DelayArgs &a, int dtype, int vec, hipStream_t s);
 hipError_t launch_zero_words(uint32_t *p, size_t words, hipStream_t s);
 hipError_t launch_combine(const float *W, const double *a_dev, int k, int64_t d, float *w_out,
                           hipStream_t s);

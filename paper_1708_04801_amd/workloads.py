@@ -14,6 +14,10 @@ the tests can ask for a small instance of the same structure:
   many_chains     dense fp32, hinge,    m=1048576  d=256    k=2048
   wide_bf16       dense bf16, logistic, m=65536    d=65536  k=32
 
+and one for the delay-SGD servers of Section IV:
+
+  delay_servers   dense fp32, logistic, m=65536    d=4096   k=128  (rows nearly along one direction)
+
 The sparse family stands in for the very wide, very sparse, hinge-loss text-like
 data the paper trains on (section V, "Real-world data"); it borrows only the
 shape class, none of that data set's records.
@@ -256,6 +260,37 @@ def analog_binary(m_train=460_000, m_test=40_000, d=100_000, n_fast=100_000, fas
     n = np.array([n_fast] * fast + [int(round(n_fast * slow_share))] * slow, dtype=np.int64)
     return Workload("analog_binary", HINGE, 1e-4, 0.01, 0, n, y, m, d, row_ptr=row_ptr, col_idx=col_idx, vals=vals,
                     meta={"m_train": m_train, "m_test": m_test, "w0": 4.0, "rate": 0.99999})
+
+
+def delay_servers(m=65536, d=4096, k=128, n_lo=2000, n_hi=8000, tau=2, loss=LOGISTIC, spread=0.01, bf16=False,
+                  data_seed=1006) -> Workload:
+    """Input for the delay-SGD servers (Section IV).  On unstructured rows the acceptance test of that
+    section throws away nearly every sample after the first, so the rows here lie close to one
+    direction u: x_j = y_j * s_j * u + noise, s_j uniform in [0.6, 1], |u| = 1, noise of total length
+    about `spread`.  Successive projections then move the same way and servers make tens of updates.
+    meta: the delay tau and a common non-zero start vector (float32)."""
+    ss = np.random.SeedSequence(data_seed)
+    s_u, s_x, s_n, s_w = ss.spawn(4)
+    u = np.random.default_rng(s_u).standard_normal(d)
+    u = (u / np.linalg.norm(u)).astype(np.float32)
+    X = np.empty((m, d), dtype=np.uint16 if bf16 else np.float32)
+    y = np.empty(m, dtype=np.float32)
+    blocks = _blocks(m, max(1, min(m, (1 << 24) // max(d, 1))))
+
+    def fill(lo, hi, rng):
+        lab = np.where(rng.random(hi - lo) < 0.5, 1.0, -1.0).astype(np.float32)
+        length = (0.6 + 0.4 * rng.random(hi - lo)).astype(np.float32)
+        blk = rng.standard_normal((hi - lo, d), dtype=np.float32)
+        blk *= np.float32(spread / np.sqrt(d))
+        blk += np.outer(lab * length, u)
+        X[lo:hi] = f32_to_bf16_bits(blk) if bf16 else blk
+        y[lo:hi] = lab
+        return None
+
+    _run_blocks(fill, blocks, s_x.spawn(len(blocks)))
+    n = np.random.default_rng(s_n).integers(n_lo, n_hi + 1, size=k).astype(np.int64)
+    w_start = (np.random.default_rng(s_w).standard_normal(d) * (1.0 / np.sqrt(d))).astype(np.float32)
+    return Workload("delay_servers", loss, 0.5, 0.25, 0, n, y, m, d, dense=X, meta={"tau": tau, "w_start": w_start})
 
 
 FULL = {
