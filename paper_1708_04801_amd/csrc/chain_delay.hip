@@ -13,6 +13,13 @@
 //     w_{J+1} = w_J - eta*lambda*w_{J-tau} - eta*u*x          (the recurrence in the proof of Lemma 4)
 // together with its squared length, which later tests need for the part across a sample,
 // |w|^2 - L^2/beta^2.  All arithmetic is fp64; the result is rounded to fp32 once, at the end.
+//
+// Two kernels.  delay_server_reg_kernel holds the ring in registers, newest iterate first, and shifts
+// it when a candidate is accepted; the rows of the next samples (which do not depend on what is
+// accepted) are requested PF samples ahead, so a sample costs the pass over its row, one exchange of
+// sums and the decision.  It covers rows of up to 256 x EPT aligned elements and delays up to 4.
+// delay_server_kernel keeps the ring in the workspace and covers everything else.
+#include "dense_rows.h"
 #include "device_utils.h"
 #include "internal.h"
 
@@ -58,6 +65,27 @@ __device__ inline bool check_triple(double La, double Lb, double Lc, double pa, 
     const double Lmin = (Lb - rate * La) / (1.0 - rate);
     const double lo = Lmin < Lb ? Lmin : Lb, hi = Lmin < Lb ? Lb : Lmin;
     return lo <= Lc && Lc <= hi && !(pb > pa);
+}
+
+// The same with 1/(1 - rate) at hand (rate < 1 is the caller's business): the register kernel forms it
+// once per sample for all its triples.
+__device__ inline bool check_triple_scaled(double La, double Lb, double Lc, double pa, double pb, double rate,
+                                           double inv_one_minus_rate)
+{
+    const double Lmin = (Lb - rate * La) * inv_one_minus_rate;
+    const double lo = Lmin < Lb ? Lmin : Lb, hi = Lmin < Lb ? Lb : Lmin;
+    return lo <= Lc && Lc <= hi && !(pb > pa);
+}
+
+// base^(1/REACH) for the delays the register kernel covers, by square and cube roots.
+template <int REACH>
+__device__ inline double delay_root(double base)
+{
+    if constexpr (REACH == 1) return base;
+    else if constexpr (REACH == 2) return sqrt(base);
+    else if constexpr (REACH == 3) return cbrt(base);
+    else if constexpr (REACH == 4) return sqrt(sqrt(base));
+    else return pow(base, 1.0 / (double)REACH);
 }
 
 // MAXW: how many iterates one pass can project (reach + 1 are needed).
@@ -215,6 +243,185 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_kernel(DelayArgs a
     if (tid == 0) a.accepted[chain] = J;
 }
 
+// The ring in registers.  R1 = max(tau, 1) + 1 iterates are kept: r[i] is w_{J-i}; before J reaches i
+// the slot holds w_0, which is what an index below zero means.  n2[i] is |w_{J-i}|^2.
+template <typename TX, int EPT, int VEC, int R1, int PF>
+__global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayArgs a)
+{
+    constexpr int NT = kDelayThreads, NW = kDelayWaves;
+    using Frag = RowFrag<TX, NT, EPT, VEC>;
+    __shared__ double red[2][NW][R1 + 1];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int chain = blockIdx.x;
+    const int64_t n = a.n_samples[chain];
+    const uint32_t d = (uint32_t)a.d;
+    const char *X = static_cast<const char *>(a.dense);
+    const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
+    const uint32_t row_bytes = d * (uint32_t)sizeof(TX);
+    const double eta = a.eta, eta_lambda = a.eta * a.lambda;
+    const bool no_delay = a.tau == 0;
+    int parity = 0;
+
+    // element e of this thread is column col0[e / VEC] + e % VEC; columns from d on do not exist
+    uint32_t off[Frag::kChunks];
+#pragma unroll
+    for (int c = 0; c < Frag::kChunks; ++c) off[c] = (uint32_t)((c * NT + tid) * VEC) * (uint32_t)sizeof(TX);
+    auto column = [&](int e) { return (uint32_t)(((e / VEC) * NT + tid) * VEC + e % VEC); };
+
+    auto block_sums = [&](auto &v, auto count_tag) {
+        constexpr int COUNT = decltype(count_tag)::value;
+#pragma unroll
+        for (int t = 0; t < COUNT; ++t) {
+            const double w = wave_sum_lane63(v[t]);
+            if (lane == kWave - 1) red[parity][wave][t] = w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < COUNT; ++t) {
+            double sum = red[parity][0][t];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) sum += red[parity][w][t];
+            v[t] = sum;
+        }
+        parity ^= 1;
+    };
+
+    double r[R1][EPT], n2[R1];
+    {
+        double v[1] = {0.0};
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const uint32_t col = column(e);
+            const double w = (a.w_start && col < d) ? (double)a.w_start[col] : 0.0;
+#pragma unroll
+            for (int i = 0; i < R1; ++i) r[i][e] = w;
+            v[0] += w * w;
+        }
+        block_sums(v, std::integral_constant<int, 1>{});
+#pragma unroll
+        for (int i = 0; i < R1; ++i) n2[i] = v[0];
+    }
+
+    RowWindow win;
+    win.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
+    Frag x[PF];
+    float ys[PF];
+    auto request = [&](int u, int64_t s) {
+        const uint32_t row = win.get(s);
+        const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (int64_t)row * row_stride, row_bytes);
+#pragma unroll
+        for (int c = 0; c < Frag::kChunks; ++c) x[u].load_chunk(c, rx, off[c]);
+        ys[u] = a.y[row];
+    };
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u < n) request(u, u);
+
+    int64_t J = 0;
+    for (int64_t s0 = 0; s0 < n; s0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int64_t s = s0 + u;
+            if (s >= n) break;
+            double xe[EPT];
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) xe[e] = (double)x[u].at(e);
+            const double y = (double)ys[u];
+            if (s + PF < n) request(u, s + PF);
+
+            double v[R1 + 1];                        // v[i] = w_{J-i}.x, v[R1] = x.x
+#pragma unroll
+            for (int i = 0; i <= R1; ++i) v[i] = 0.0;
+            if (a.check) {
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+                    v[R1] += xe[e] * xe[e];
+#pragma unroll
+                    for (int i = 0; i < R1; ++i) v[i] += r[i][e] * xe[e];
+                }
+                block_sums(v, std::integral_constant<int, R1 + 1>{});
+            } else {                                 // only the projection the gradient needs
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) v[0] += (no_delay ? r[0][e] : r[R1 - 1][e]) * xe[e];
+                block_sums(v, std::integral_constant<int, 1>{});
+                v[R1 - 1] = v[0];
+            }
+            const double beta2 = v[R1];
+            const double yhat = no_delay ? v[0] : v[R1 - 1];           // the gradient is taken at w_{J-tau}
+            const double g = a.loss == kLossHinge ? loss_slope<kLossHinge>(y, yhat) : loss_slope<kLossLogistic>(y, yhat);
+
+            bool keep = true;
+            if (a.check) {
+                const double rate = delay_root<R1 - 1>(eta_lambda + eta * beta2);
+                keep = rate < 1.0;
+                const double inv_b2 = beta2 > 0.0 ? 1.0 / beta2 : 0.0, inv_1r = 1.0 / (1.0 - rate);
+                double across[R1];                   // squared length of the part of w_{J-i} across x
+#pragma unroll
+                for (int i = 0; i < R1; ++i) across[i] = n2[i] - v[i] * v[i] * inv_b2;
+                // first call: triples (w_{J-i-2}, w_{J-i-1}, w_{J-i}) inside the window that exist
+#pragma unroll
+                for (int i = 0; i + 2 < R1; ++i)
+                    if (J >= i + 2)
+                        keep = keep && check_triple_scaled(v[i + 2], v[i + 1], v[i], across[i + 2], across[i + 1], rate, inv_1r);
+                if (J >= 1) {
+                    const double L_cand = v[0] - eta_lambda * yhat - eta * g * beta2;
+                    keep = keep && check_triple_scaled(v[1], v[0], L_cand, across[1], across[0], rate, inv_1r);
+                }
+            }
+            if (keep) {
+                const double eg = eta * g;
+                double u2[1] = {0.0};
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+                    const double old = no_delay ? r[0][e] : r[R1 - 1][e];
+                    const double w = r[0][e] - eta_lambda * old - eg * xe[e];
+#pragma unroll
+                    for (int i = R1 - 1; i >= 1; --i) r[i][e] = r[i - 1][e];
+                    r[0][e] = w;
+                    u2[0] += w * w;
+                }
+                block_sums(u2, std::integral_constant<int, 1>{});
+#pragma unroll
+                for (int i = R1 - 1; i >= 1; --i) n2[i] = n2[i - 1];
+                n2[0] = u2[0];
+                ++J;
+            }
+        }
+    }
+
+    float *out = a.W + (int64_t)chain * a.d;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const uint32_t col = column(e);
+        if (col < d) out[col] = (float)r[0][e];
+    }
+    if (tid == 0) a.accepted[chain] = J;
+}
+
+constexpr int kDelayRegMaxTau = 4;
+constexpr int kDelayAhead = 2;          // samples whose rows are in flight
+
+// Launches the register kernel if one is built for this shape; *done tells.
+template <typename TX, int VEC>
+hipError_t launch_reg(const DelayArgs &a, hipStream_t s, bool *done)
+{
+    const int r1 = (a.tau > 1 ? a.tau : 1) + 1;
+    *done = true;
+#define WPSGD_DELAY_REG(EPT, R1)                                                                                 \
+    if (a.d <= (int64_t)kDelayThreads * EPT && r1 == R1) {                                                       \
+        hipLaunchKernelGGL((delay_server_reg_kernel<TX, EPT, VEC, R1, kDelayAhead>), dim3(a.k), dim3(kDelayThreads), 0, s, a); \
+        return hipGetLastError();                                                                                \
+    }
+    WPSGD_DELAY_REG(8, 2) WPSGD_DELAY_REG(8, 3) WPSGD_DELAY_REG(8, 4) WPSGD_DELAY_REG(8, 5)
+    WPSGD_DELAY_REG(16, 2) WPSGD_DELAY_REG(16, 3) WPSGD_DELAY_REG(16, 4) WPSGD_DELAY_REG(16, 5)
+#undef WPSGD_DELAY_REG
+    *done = false;
+    return hipSuccess;
+}
+
 template <typename TX, int VEC>
 hipError_t launch_reach(const DelayArgs &a, hipStream_t s)
 {
@@ -235,6 +442,11 @@ hipError_t launch_reach(const DelayArgs &a, hipStream_t s)
 
 hipError_t launch_delay_servers(const DelayArgs &a, int dtype, int vec, hipStream_t s)
 {
+    if (vec > 1 && a.tau <= kDelayRegMaxTau && a.d * (dtype == WPSGD_BF16 ? 2 : 4) < (int64_t)1 << 31) {
+        bool done = false;
+        const hipError_t e = dtype == WPSGD_BF16 ? launch_reg<uint16_t, 8>(a, s, &done) : launch_reg<float, 4>(a, s, &done);
+        if (done) return e;
+    }
     if (dtype == WPSGD_BF16) return vec > 1 ? launch_reach<uint16_t, 8>(a, s) : launch_reach<uint16_t, 1>(a, s);
     return vec > 1 ? launch_reach<float, 4>(a, s) : launch_reach<float, 1>(a, s);
 }

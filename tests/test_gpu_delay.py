@@ -78,6 +78,16 @@ def test_servers_under_check(tau, loss, d, bf16):
     assert acc_o.max() >= 4 and (acc_o < w.n_steps).all()      # samples are taken and samples are thrown away
 
 
+@pytest.mark.parametrize("tau", [0, 1, 3, 4])
+@pytest.mark.parametrize("d,bf16", [(4096, False), (3584, True)])
+def test_servers_under_check_on_rows_of_the_measured_width(tau, d, bf16):
+    w = wl.delay_servers(m=2048, d=d, k=6, n_lo=500, n_hi=1500, tau=tau, bf16=bf16, data_seed=90 + tau)
+    Wg, acc_g, Wo, acc_o, gap = run_both(w, tau, check=True)
+    compare(Wg, acc_g, Wo, acc_o, gap, f"check tau={tau} d={d}", max_ties=1)
+    Wg, acc_g, Wo, acc_o, gap = run_both(w, tau, check=False)
+    compare(Wg, acc_g, Wo, acc_o, gap, f"plain tau={tau} d={d}")
+
+
 def test_check_from_the_zero_start_of_algorithm_3():
     """From w_0 = 0 nothing lies across the second sample yet while w_1 does, so the second update passes
     only for a sample parallel to the first, and then the comparison of the two parts is a tie."""
