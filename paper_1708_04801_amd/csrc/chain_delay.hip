@@ -56,6 +56,32 @@ template <> struct DelayRow<uint16_t, 8> {
     }
 };
 
+// N fp64 wave sums at once, level by level: the moves of one level are independent of each other, so
+// none has to wait for the addition before it (a DPP operand written by the instruction just before
+// costs idle slots).  Per value the additions and their order are those of wave_sum_lane63; the
+// totals are valid in lane 63.
+template <int CTRL, int N>
+__device__ inline void wave_sums_level(double (&v)[N], int count)
+{
+    double moved[N];
+#pragma unroll
+    for (int t = 0; t < N; ++t)
+        if (t < count) moved[t] = dpp_move<CTRL, 0xF>(v[t]);
+#pragma unroll
+    for (int t = 0; t < N; ++t)
+        if (t < count) v[t] += moved[t];
+}
+template <int N>
+__device__ inline void wave_sums_lane63(double (&v)[N], int count)
+{
+    wave_sums_level<0xB1>(v, count);
+    wave_sums_level<0x4E>(v, count);
+    wave_sums_level<0x141>(v, count);
+    wave_sums_level<0x140>(v, count);
+    wave_sums_level<0x142>(v, count);
+    wave_sums_level<0x143>(v, count);
+}
+
 // One triple of Algorithm 4: the newest projection must lie between the middle one and
 // Length_min = (L_b - rate*L_a)/(1 - rate), ends included, and the part of the middle iterate across
 // the sample (squared length pb) must not be longer than that of the oldest (pa).
@@ -67,14 +93,20 @@ __device__ inline bool check_triple(double La, double Lb, double Lc, double pa, 
     return lo <= Lc && Lc <= hi && !(pb > pa);
 }
 
-// The same with 1/(1 - rate) at hand (rate < 1 is the caller's business): the register kernel forms it
-// once per sample for all its triples.
-__device__ inline bool check_triple_scaled(double La, double Lb, double Lc, double pa, double pb, double rate,
-                                           double inv_one_minus_rate)
+// The two halves of that test without a division, as the register kernel takes them (rate < 1 and
+// beta2 > 0 are the caller's business; only comparisons that sit within rounding of a tie can differ).
+// Between L_b and Length_min: multiply the three numbers by 1 - rate > 0.
+__device__ inline bool inside_interval(double La, double Lb, double Lc, double rate)
 {
-    const double Lmin = (Lb - rate * La) * inv_one_minus_rate;
-    const double lo = Lmin < Lb ? Lmin : Lb, hi = Lmin < Lb ? Lb : Lmin;
-    return lo <= Lc && Lc <= hi && !(pb > pa);
+    const double s = 1.0 - rate;
+    const double e0 = s * Lb, e1 = Lb - rate * La, c = s * Lc;
+    const double lo = e1 < e0 ? e1 : e0, hi = e1 < e0 ? e0 : e1;
+    return lo <= c && c <= hi;
+}
+// |b|^2 - L_b^2/beta2 <= |a|^2 - L_a^2/beta2, multiplied by beta2.
+__device__ inline bool across_does_not_grow(double La, double Lb, double na2, double nb2, double beta2)
+{
+    return !((nb2 - na2) * beta2 > Lb * Lb - La * La);
 }
 
 // base^(1/REACH) for the delays the register kernel covers, by square and cube roots.
@@ -262,7 +294,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayAr
     const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
     const uint32_t row_bytes = d * (uint32_t)sizeof(TX);
     const double eta = a.eta, eta_lambda = a.eta * a.lambda;
-    const bool no_delay = a.tau == 0;
+    const bool no_delay = R1 == 2 && a.tau == 0;    // with three or more iterates kept the delay is R1 - 1
     int parity = 0;
 
     // element e of this thread is column col0[e / VEC] + e % VEC; columns from d on do not exist
@@ -273,11 +305,10 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayAr
 
     auto block_sums = [&](auto &v, auto count_tag) {
         constexpr int COUNT = decltype(count_tag)::value;
+        wave_sums_lane63(v, COUNT);
 #pragma unroll
-        for (int t = 0; t < COUNT; ++t) {
-            const double w = wave_sum_lane63(v[t]);
-            if (lane == kWave - 1) red[parity][wave][t] = w;
-        }
+        for (int t = 0; t < COUNT; ++t)
+            if (lane == kWave - 1) red[parity][wave][t] = v[t];
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < COUNT; ++t) {
@@ -351,25 +382,37 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayAr
             }
             const double beta2 = v[R1];
             const double yhat = no_delay ? v[0] : v[R1 - 1];           // the gradient is taken at w_{J-tau}
-            const double g = a.loss == kLossHinge ? loss_slope<kLossHinge>(y, yhat) : loss_slope<kLossLogistic>(y, yhat);
 
+            // The cheapest tests come first and a failed one ends the sample: the parts across x (no root,
+            // no slope), then the intervals of the first call (the root), then the candidate's (the slope).
             bool keep = true;
+            double g = 0.0;
             if (a.check) {
-                const double rate = delay_root<R1 - 1>(eta_lambda + eta * beta2);
-                keep = rate < 1.0;
-                const double inv_b2 = beta2 > 0.0 ? 1.0 / beta2 : 0.0, inv_1r = 1.0 / (1.0 - rate);
-                double across[R1];                   // squared length of the part of w_{J-i} across x
+                if (beta2 > 0.0) {
 #pragma unroll
-                for (int i = 0; i < R1; ++i) across[i] = n2[i] - v[i] * v[i] * inv_b2;
-                // first call: triples (w_{J-i-2}, w_{J-i-1}, w_{J-i}) inside the window that exist
+                    for (int i = 0; i + 1 < R1; ++i)      // pairs (w_{J-i-1}, w_{J-i}) that some triple holds
+                        if (J >= i + 1) keep = keep && across_does_not_grow(v[i + 1], v[i], n2[i + 1], n2[i], beta2);
+                } else {
 #pragma unroll
-                for (int i = 0; i + 2 < R1; ++i)
-                    if (J >= i + 2)
-                        keep = keep && check_triple_scaled(v[i + 2], v[i + 1], v[i], across[i + 2], across[i + 1], rate, inv_1r);
-                if (J >= 1) {
-                    const double L_cand = v[0] - eta_lambda * yhat - eta * g * beta2;
-                    keep = keep && check_triple_scaled(v[1], v[0], L_cand, across[1], across[0], rate, inv_1r);
+                    for (int i = 0; i + 1 < R1; ++i)
+                        if (J >= i + 1) keep = keep && !(n2[i] > n2[i + 1]);
                 }
+                if (keep) {
+                    const double rate = delay_root<R1 - 1>(eta_lambda + eta * beta2);
+                    keep = rate < 1.0 || J == 0;          // with no triple to test nothing is rejected
+#pragma unroll
+                    for (int i = 0; i + 2 < R1; ++i)
+                        if (J >= i + 2) keep = keep && inside_interval(v[i + 2], v[i + 1], v[i], rate);
+                    if (keep && J >= 1) {
+                        g = a.loss == kLossHinge ? loss_slope<kLossHinge>(y, yhat) : loss_slope<kLossLogistic>(y, yhat);
+                        const double L_cand = v[0] - eta_lambda * yhat - eta * g * beta2;
+                        keep = inside_interval(v[1], v[0], L_cand, rate);
+                    } else if (keep) {
+                        g = a.loss == kLossHinge ? loss_slope<kLossHinge>(y, yhat) : loss_slope<kLossLogistic>(y, yhat);
+                    }
+                }
+            } else {
+                g = a.loss == kLossHinge ? loss_slope<kLossHinge>(y, yhat) : loss_slope<kLossLogistic>(y, yhat);
             }
             if (keep) {
                 const double eg = eta * g;

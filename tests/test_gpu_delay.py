@@ -97,6 +97,17 @@ def test_check_from_the_zero_start_of_algorithm_3():
     assert (acc_o[gap >= TIE] == 1).all() and (acc_g >= 1).all()
 
 
+@pytest.mark.parametrize("d", [1024, 1001])
+def test_rows_too_long_for_a_contraction_are_all_rejected_after_the_first(d):
+    """eta*lambda + eta*|x|^2 >= 1 leaves no interval: once there is a triple to test nothing passes, but
+    the first update has none and is made."""
+    w = wl.delay_servers(m=256, d=d, k=4, n_lo=20, n_hi=60, tau=2, data_seed=17)
+    w.dense *= np.float32(3.0)
+    Wg, acc_g, Wo, acc_o, gap = run_both(w, 2, check=True)
+    assert acc_o.tolist() == [1, 1, 1, 1]
+    compare(Wg, acc_g, Wo, acc_o, gap, f"long rows d={d}")
+
+
 def test_hand_worked_servers():
     """The two servers worked by hand for the oracle's pins (exact binary fractions), through the GPU."""
     X = api.Matrix(1, 2, dense=torch.tensor([[1.0, 0.0]], device="cuda"))
