@@ -1,29 +1,37 @@
-// Sparse-row (CSR) SGD chains, two wavefronts per chain.
+// Sparse-row (CSR) SGD chains, three wavefronts per chain.
 //
 // A step of a sparse chain is a short dependent recursion (gather the model at the row's columns,
 // reduce, decide, scatter), and one wavefront issues one instruction at a time: with a single
 // wave the step is bound by the number of instructions in it, and most of those do not depend on
 // the model at all - finding the row, fetching its entries, sorting columns into "kept in LDS"
-// and "kept in HBM", computing addresses.  This kernel gives that part to a second wave:
+// and "kept in HBM", computing addresses, deciding whether an early fetch can be stale.  This
+// kernel gives that part to two more waves, each on a SIMD of its own:
 //
-//   scout   walks the chain's sample stream ahead of the worker.  For every step it fetches the
-//           row's entries and writes one 16-byte record per entry into an LDS ring: the value,
-//           the LDS address of the model element (or of a scratch slot), the offset of the model
-//           element in the HBM-resident part of the vector (or an offset past its end, which the
-//           hardware turns into no access at all), and whether it is one.  It also writes the
-//           per-step scalars of the recursion and whether the step must re-read its values.
+//   record scout  walks the chain's sample stream ahead of the worker.  For every step it fetches
+//           the row's entries (last entry first, so that the HBM-resident columns of a row, its
+//           highest, share the first load) and writes one 16-byte record per entry into an LDS
+//           ring: the value, the LDS address of the model element (or of a scratch slot), the
+//           offset of the model element in the HBM-resident part of the vector (or an offset past
+//           its end, which the hardware turns into no access at all), and whether it is one.  It
+//           also writes the per-step scalars of the recursion.
+//   stamp scout   walks the same stream, keeps the stamp tables described below and marks the
+//           steps that must read their values again.
 //   worker  runs the recursion of Eq. 5 (w = s*v, the shrink carried by the scalar s) from the
 //           records: all its loads, stores and LDS accesses are unconditional and their
 //           addresses come ready-made.
 //
-// The ring has three sections of kG steps.  One barrier per section keeps the two waves in step:
-// the scout passes barrier i after writing section i, the worker passes it before it starts
-// section i-1, whose steps read records of sections i-1 and i; so the scout is always writing
-// the one section the worker is not reading.  Both waves execute the same number of barriers.
+// The model vector's HBM-resident part is prepared before this kernel and turned into W after it
+// by two wide kernels (csr_state_start_kernel, csr_state_finish_kernel), so a chain does no work
+// proportional to d.
+//
+// The ring has three sections of kG steps.  One barrier per section keeps the waves in step:
+// the scouts pass barrier i after writing section i, the worker passes it before it starts
+// section i-1, whose steps read records of sections i-1 and i; so the scouts are always writing
+// the one section the worker is not reading.  All waves execute the same number of barriers.
 //
 // Model values: columns below kPHead live in LDS; the others stay in HBM and are requested kTQ
 // steps ahead.  A value fetched early is stale if a step in between wrote the same column.  Whether
-// that can have happened depends on the rows alone, not on the model, so the scout decides it: it
+// that can have happened depends on the rows alone, not on the model, so the stamp scout decides it: it
 // keeps two LDS stamp tables (two different hashes of the column) with the step number of the last
 // write to each slot, and a step that finds recent numbers in both slots of one of its columns is
 // marked; the worker drains the memory queue and reads that step's values again.  A write always

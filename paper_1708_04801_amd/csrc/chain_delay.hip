@@ -445,7 +445,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayAr
 }
 
 constexpr int kDelayRegMaxTau = 4;
-constexpr int kDelayAhead = 2;          // samples whose rows are in flight
+constexpr int kDelayAhead = 4;          // samples whose rows are in flight
 
 // Launches the register kernel if one is built for this shape; *done tells.
 template <typename TX, int VEC>
