@@ -112,7 +112,8 @@ def bench_delay_servers(args, torch, api, wl) -> int:
                    "loss": "hinge" if w.loss == wl.HINGE else "logistic",
                    "accepted_updates_min_mean_max": [int(acc.min()), float(acc.mean()), int(acc.max())]},
         "roofline": {"bound": "hbm", "kernel": "delay_server_kernel (wpsgd_run_delay_chains)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic("delay_servers") if check else None,
                      "bytes_per_sample": bytes_per_sample, "kernel_ms": kernel_ms,
                      "most_samples_one_server": int(w.n_steps.max()),
                      "us_per_sample_busiest_server": kernel_ms * 1e3 / max(1, int(w.n_steps.max()))},
