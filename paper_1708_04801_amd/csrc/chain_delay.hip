@@ -14,11 +14,15 @@
 // together with its squared length, which later tests need for the part across a sample,
 // |w|^2 - L^2/beta^2.  All arithmetic is fp64; the result is rounded to fp32 once, at the end.
 //
-// Two kernels.  delay_server_reg_kernel holds the ring in registers, newest iterate first, and shifts
+// Three kernels.  delay_server_reg_kernel holds the ring in registers, newest iterate first, and shifts
 // it when a candidate is accepted; the rows of the next samples (which do not depend on what is
 // accepted) are requested PF samples ahead, so a sample costs the pass over its row, one exchange of
 // sums and the decision.  It covers rows of up to 256 x EPT aligned elements and delays up to 4.
-// delay_server_kernel keeps the ring in the workspace and covers everything else.
+// delay_server_batch_kernel is the same under the Check function, where nearly every sample is thrown
+// away: it decides B samples per exchange, rows staged in LDS.  delay_server_kernel keeps the ring in
+// the workspace and covers everything else.
+#include <atomic>
+
 #include "dense_rows.h"
 #include "device_utils.h"
 #include "internal.h"
@@ -101,7 +105,7 @@ __device__ inline bool inside_interval(double La, double Lb, double Lc, double r
     const double s = 1.0 - rate;
     const double e0 = s * Lb, e1 = Lb - rate * La, c = s * Lc;
     const double lo = e1 < e0 ? e1 : e0, hi = e1 < e0 ? e0 : e1;
-    return lo <= c && c <= hi;
+    return (lo <= c) & (c <= hi);
 }
 // |b|^2 - L_b^2/beta2 <= |a|^2 - L_a^2/beta2, multiplied by beta2.
 __device__ inline bool across_does_not_grow(double La, double Lb, double na2, double nb2, double beta2)
@@ -444,8 +448,288 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayAr
     if (tid == 0) a.accepted[chain] = J;
 }
 
+// All tests of the Check function for one sample, from its scalars alone and without branches on the
+// data: L[i] = w_{J-i}.x for i < R1, L[R1] = x.x; n2[i] = |w_{J-i}|^2; yhat and g belong to w_{J-tau}.
+template <int R1>
+__device__ inline bool window_passes(const double *L, const double (&n2)[R1], int64_t J, double eta, double eta_lambda,
+                                     double yhat, double g)
+{
+    // (bitwise and/or on purpose: nothing here is worth a branch, and without branches the tests of
+    // several samples can be interleaved)
+    const double beta2 = L[R1];
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i + 1 < R1; ++i) {          // pairs (w_{J-i-1}, w_{J-i}) that some triple holds
+        const bool along = across_does_not_grow(L[i + 1], L[i], n2[i + 1], n2[i], beta2);
+        const bool plain = !(n2[i] > n2[i + 1]);
+        ok = ok & ((J < i + 1) | (beta2 > 0.0 ? along : plain));
+    }
+    const double rate = delay_root<R1 - 1>(eta_lambda + eta * beta2);
+    ok = ok & ((rate < 1.0) | (J == 0));        // with no triple to test nothing is rejected
+#pragma unroll
+    for (int i = 0; i + 2 < R1; ++i) ok = ok & ((J < i + 2) | inside_interval(L[i + 2], L[i + 1], L[i], rate));
+    const double L_cand = L[0] - eta_lambda * yhat - eta * g * beta2;
+    ok = ok & ((J < 1) | inside_interval(L[1], L[0], L_cand, rate));
+    return ok;
+}
+
+// Under the Check function nearly every sample is thrown away, and a sample that is thrown away leaves
+// the ring as it was.  This kernel therefore looks at B samples at once: it projects the ring on all B
+// rows, exchanges the B x (R1 + 1) sums in one round and takes the B decisions side by side in
+// straight-line code (so that their dependent fp64 chains overlap), each as if the samples before it had
+// been rejected.  The decisions up to and including the first acceptance are then the sequential ones;
+// that sample's candidate is written and the samples behind it are looked at again, against the new ring,
+// as the next batch.
+//
+// Rows travel from HBM straight into a ring of S row slots in LDS (sample s in slot s mod S), loads that
+// need no registers while in flight: the rows of samples pos .. pos+S-1 are always there or on their way,
+// so a batch's rows were asked for at least S-B samples earlier, and the row of an accepted sample is
+// still in its slot when the candidate is formed.  Each wave reads back only what its own loads wrote,
+// so the slots need no barrier.  The compiler does not see these loads; the one wait they need is placed
+// by hand: a wave's loads complete in issue order, so "at most (S-B) samples' worth outstanding" means
+// the batch has landed.  Samples from n on are asked for all the same (their last valid row again) so
+// that this count is a constant.
+template <typename TX, int EPT, int VEC, int R1, int B, int S>
+__global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(DelayArgs a)
+{
+    constexpr int NT = kDelayThreads, NW = kDelayWaves, NV = B * (R1 + 1);
+    using Frag = RowFrag<TX, NT, EPT, VEC>;
+    static_assert(VEC * sizeof(TX) == 16, "16-byte loads only");
+    constexpr int CHUNKS = EPT / VEC;
+    static_assert(Frag::kWords == 4 * CHUNKS, "four words per chunk");
+    constexpr uint32_t kWaveBytes = CHUNKS * kWave * 16;          // what one wave holds of one row
+    constexpr uint32_t kSlotBytes = NW * kWaveBytes;
+    constexpr int kLoadsPerSample = CHUNKS + 1;                   // the row's chunks and its label
+    static_assert((S - B) * kLoadsPerSample < 64, "the wait below counts up to 63 loads");
+    constexpr uint32_t kLabelBytes = kWave * 4;                   // a wave's copy of one sample's label (64 times)
+    extern __shared__ __attribute__((aligned(16))) uint32_t stage[];     // S slots of kSlotBytes, then S x NW label pads
+    __shared__ double red[2][NW][NV];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int chain = blockIdx.x;
+    const int64_t n = a.n_samples[chain];
+    const uint32_t d = (uint32_t)a.d;
+    const char *X = static_cast<const char *>(a.dense);
+    const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
+    const uint32_t row_bytes = d * (uint32_t)sizeof(TX);
+    const double eta = a.eta, eta_lambda = a.eta * a.lambda;
+    const bool no_delay = R1 == 2 && a.tau == 0;
+    int parity = 0;
+
+    auto column = [&](int e) { return (uint32_t)(((e / VEC) * NT + tid) * VEC + e % VEC); };
+
+    auto block_sums = [&](auto &v, auto count_tag) {
+        constexpr int COUNT = decltype(count_tag)::value;
+        wave_sums_lane63(v, COUNT);
+#pragma unroll
+        for (int t = 0; t < COUNT; ++t)
+            if (lane == kWave - 1) red[parity][wave][t] = v[t];
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < COUNT; ++t) {
+            double sum = red[parity][0][t];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) sum += red[parity][w][t];
+            v[t] = sum;
+        }
+        parity ^= 1;
+    };
+
+    double r[R1][EPT], n2[R1];
+    {
+        double v[1] = {0.0};
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const uint32_t col = column(e);
+            const double w = (a.w_start && col < d) ? (double)a.w_start[col] : 0.0;
+#pragma unroll
+            for (int i = 0; i < R1; ++i) r[i][e] = w;
+            v[0] += w * w;
+        }
+        block_sums(v, std::integral_constant<int, 1>{});
+#pragma unroll
+        for (int i = 0; i < R1; ++i) n2[i] = v[0];
+    }
+    if (n <= 0) {
+        float *out0 = a.W + (int64_t)chain * a.d;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const uint32_t col = column(e);
+            if (col < d) out0[col] = (float)r[0][e];
+        }
+        if (tid == 0) a.accepted[chain] = 0;
+        return;
+    }
+
+    RowWindow ahead;
+    ahead.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
+    typedef __attribute__((address_space(3))) uint32_t *lds_ptr;
+    const uint32_t stage0 = (uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)((uint32_t)(size_t)(lds_ptr)&stage[0] + (uint32_t)wave * kWaveBytes));
+    const uint32_t voff = (uint32_t)(tid * 16);                   // this lane's bytes of chunk 0; chunk c adds c*NT*16
+    const uint32_t labels0 = (uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)((uint32_t)(size_t)(lds_ptr)&stage[0] + (uint32_t)S * kSlotBytes + (uint32_t)wave * kLabelBytes));
+    const uint32_t *label_pad = stage + (size_t)S * (kSlotBytes / 4) + (size_t)wave * (kLabelBytes / 4);
+    u32x4 ry;                                                     // the labels as a buffer
+    {
+        const uint64_t base = (uint64_t)(uintptr_t)a.y;
+        ry[0] = (uint32_t)base;
+        ry[1] = (uint32_t)(base >> 32) & 0xffffu;
+        ry[2] = (uint32_t)a.m * 4u;
+        ry[3] = 0x00020000u;
+    }
+    // the label and the row of sample s (of the last sample, beyond the end) into slot s mod S; the
+    // label goes first, so it has landed when the row has.  (A label fetched by an ordinary load inside
+    // the loop would queue behind the rows on their way and wait for all of them.)
+    auto request = [&](int64_t s) {
+        const uint32_t row = ahead.get(s < n ? s : n - 1);
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                     :
+                     : "s"(labels0 + (uint32_t)(s % S) * (NW * kLabelBytes)), "v"(row * 4u), "s"(ry)
+                     : "memory", "m0");
+        const uint64_t base = (uint64_t)(uintptr_t)(X + (int64_t)row * row_stride);
+        u32x4 rx;
+        rx[0] = (uint32_t)base;
+        rx[1] = (uint32_t)(base >> 32) & 0xffffu;
+        rx[2] = row_bytes;
+        rx[3] = 0x00020000u;
+        const uint32_t slot = stage0 + (uint32_t)(s % S) * kSlotBytes;
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :
+                         : "s"(slot + c * (kWave * 16)), "v"(voff), "s"(rx), "s"(c * (NT * 16))
+                         : "memory", "m0");
+    };
+    // this thread's elements of the row in slot `slot`
+    auto take = [&](uint32_t slot, Frag &x) {
+        const uint32_t *src = stage + (size_t)slot * (kSlotBytes / 4) + (size_t)wave * (kWaveBytes / 4) + lane * 4;
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) {
+            const u32x4 q = *reinterpret_cast<const u32x4 *>(src + c * (kWave * 4));
+            x.w[4 * c + 0] = q[0];
+            x.w[4 * c + 1] = q[1];
+            x.w[4 * c + 2] = q[2];
+            x.w[4 * c + 3] = q[3];
+        }
+    };
+
+    for (int64_t s = 0; s < S; ++s) request(s);
+    int64_t J = 0, pos = 0;
+    while (pos < n) {
+        // the rows of samples pos .. pos+B-1 have landed once at most (S-B)*CHUNKS loads are outstanding
+        // (gfx9 encoding: vmcnt split over bits 3:0 and 15:14; expcnt and lgkmcnt left open)
+        constexpr int kLater = (S - B) * kLoadsPerSample;
+        __builtin_amdgcn_s_waitcnt(((kLater & 0xF) | ((kLater >> 4) << 14)) | 0x0F70);
+        __builtin_amdgcn_sched_barrier(0);
+        double y[B];
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+            y[b] = (double)__uint_as_float(label_pad[(size_t)((pos + b) % S) * (NW * kLabelBytes / 4) + lane]);
+        double v[NV];                               // v[b*(R1+1) + i] = w_{J-i}.x_b, i = R1: x_b.x_b
+#pragma unroll
+        for (int t = 0; t < NV; ++t) v[t] = 0.0;
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            Frag x;
+            take((uint32_t)((pos + b) % S), x);
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const double xe = (double)x.at(e);
+                v[b * (R1 + 1) + R1] += xe * xe;
+#pragma unroll
+                for (int i = 0; i < R1; ++i) v[b * (R1 + 1) + i] += r[i][e] * xe;
+            }
+        }
+        block_sums(v, std::integral_constant<int, NV>{});
+
+        bool keep[B];
+        double slope[B], yhat[B];
+#pragma unroll
+        for (int b = 0; b < B; ++b) yhat[b] = no_delay ? v[b * (R1 + 1)] : v[b * (R1 + 1) + R1 - 1];
+        if (a.loss == kLossHinge) {                 // (one branch for the batch, so that the B slopes share a block)
+#pragma unroll
+            for (int b = 0; b < B; ++b) slope[b] = loss_slope<kLossHinge>(y[b], yhat[b]);
+        } else {
+#pragma unroll
+            for (int b = 0; b < B; ++b) slope[b] = loss_slope<kLossLogistic>(y[b], yhat[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+            keep[b] = (pos + b < n) & window_passes<R1>(v + b * (R1 + 1), n2, J, eta, eta_lambda, yhat[b], slope[b]);
+        int taken = B;                              // the first sample of the batch that is accepted
+#pragma unroll
+        for (int b = B - 1; b >= 0; --b) taken = keep[b] ? b : taken;
+        taken = __builtin_amdgcn_readfirstlane(taken);     // (every lane holds the same sums, hence the same verdict)
+        int advance = B;
+        if (__builtin_expect(taken < B, 0)) {
+            // w_{J+1} = w_J - eta*lambda*w_{J-tau} - eta*u*x; the row is still in its slot
+            double eg = 0.0;
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+                if (b == taken) eg = eta * slope[b];
+            Frag x;
+            take((uint32_t)((pos + taken) % S), x);
+            double u2[1] = {0.0};
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const double old = no_delay ? r[0][e] : r[R1 - 1][e];
+                const double w = r[0][e] - eta_lambda * old - eg * (double)x.at(e);
+#pragma unroll
+                for (int i = R1 - 1; i >= 1; --i) r[i][e] = r[i - 1][e];
+                r[0][e] = w;
+                u2[0] += w * w;
+            }
+            block_sums(u2, std::integral_constant<int, 1>{});
+#pragma unroll
+            for (int i = R1 - 1; i >= 1; --i) n2[i] = n2[i - 1];
+            n2[0] = u2[0];
+            ++J;
+            advance = taken + 1;
+        }
+        // the slots of the samples left behind take the rows that follow the ones on their way
+        __builtin_amdgcn_s_waitcnt(0xC07F);         // (every LDS read of those slots has returned)
+#pragma unroll
+        for (int i = 0; i < B; ++i)
+            if (i < advance) request(pos + S + i);
+        pos += advance;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");           // nothing may still be landing when the wave ends
+
+    float *out = a.W + (int64_t)chain * a.d;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const uint32_t col = column(e);
+        if (col < d) out[col] = (float)r[0][e];
+    }
+    if (tid == 0) a.accepted[chain] = J;
+}
+
 constexpr int kDelayRegMaxTau = 4;
 constexpr int kDelayAhead = 4;          // samples whose rows are in flight
+constexpr int kDelayBatch = 4;          // samples looked at side by side under Check
+constexpr int kDelaySlots = 8;          // rows in LDS or on their way there
+
+// The batch kernel claims S row slots of LDS, which is more than a kernel may have without asking.
+template <typename TX, int EPT, int VEC, int R1>
+bool launch_batch(const DelayArgs &a, hipStream_t s)
+{
+    auto kernel = delay_server_batch_kernel<TX, EPT, VEC, R1, kDelayBatch, kDelaySlots>;
+    constexpr size_t bytes = (size_t)kDelaySlots * kDelayWaves * ((EPT / VEC) * kWave * 16 + kWave * 4);
+    static std::atomic<int> allowed{0};             // 0 not asked yet, 1 granted, -1 refused (asking twice is harmless)
+    int may = allowed.load(std::memory_order_relaxed);
+    if (may == 0) {
+        may = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)bytes) == hipSuccess ? 1 : -1;
+        if (may < 0) (void)hipGetLastError();
+        allowed.store(may, std::memory_order_relaxed);
+    }
+    if (may < 0) return false;                      // the per-sample kernel serves instead
+    hipLaunchKernelGGL(kernel, dim3(a.k), dim3(kDelayThreads), bytes, s, a);
+    return true;
+}
 
 // Launches the register kernel if one is built for this shape; *done tells.
 template <typename TX, int VEC>
@@ -455,7 +739,10 @@ hipError_t launch_reg(const DelayArgs &a, hipStream_t s, bool *done)
     *done = true;
 #define WPSGD_DELAY_REG(EPT, R1)                                                                                 \
     if (a.d <= (int64_t)kDelayThreads * EPT && r1 == R1) {                                                       \
-        hipLaunchKernelGGL((delay_server_reg_kernel<TX, EPT, VEC, R1, kDelayAhead>), dim3(a.k), dim3(kDelayThreads), 0, s, a); \
+        if (a.check && a.m < (1 << 30) && launch_batch<TX, EPT, VEC, R1>(a, s))                                                   \
+            return hipGetLastError();                                                                            \
+        else                                                                                                     \
+            hipLaunchKernelGGL((delay_server_reg_kernel<TX, EPT, VEC, R1, kDelayAhead>), dim3(a.k), dim3(kDelayThreads), 0, s, a); \
         return hipGetLastError();                                                                                \
     }
     WPSGD_DELAY_REG(8, 2) WPSGD_DELAY_REG(8, 3) WPSGD_DELAY_REG(8, 4) WPSGD_DELAY_REG(8, 5)
