@@ -616,6 +616,10 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
         }
     };
 
+    // Lanes whose columns lie beyond the row are out of the buffer's range: whether such a load writes
+    // zeros or nothing, the slots read as zero there once they have been cleared.
+    for (uint32_t i = (uint32_t)tid; i < (uint32_t)S * (kSlotBytes / 4); i += NT) stage[i] = 0u;
+    __syncthreads();
     for (int64_t s = 0; s < S; ++s) request(s);
     int64_t J = 0, pos = 0;
     while (pos < n) {

@@ -78,3 +78,23 @@ def test_analog_binary_follows_the_papers_recipe():
         score = sum(((i + 1) % 4) * (-1) ** (i + 1) for i in c.tolist())           # the paper's labelling rule
         assert w.y[r] == (1.0 if score > 0 else -1.0)
     assert 0.2 < (w.y > 0).mean() < 0.8
+
+
+def test_delay_servers_rows_lie_close_to_one_direction():
+    w = wl.delay_servers(m=1024, d=256, k=8, n_lo=30, n_hi=90, tau=3)
+    assert w.dense.shape == (1024, 256) and w.dense.dtype == np.float32 and w.loss == wl.LOGISTIC
+    assert w.meta["tau"] == 3 and w.meta["w_start"].dtype == np.float32 and w.meta["w_start"].shape == (256,)
+    assert set(np.unique(w.y)) == {-1.0, 1.0} and 30 <= w.n_steps.min() and w.n_steps.max() <= 90
+    # x_j = y_j * s_j * u + noise: the label-signed rows share one direction, lengths 0.6 .. 1, little across it
+    X = w.dense.astype(np.float64) * w.y[:, None]
+    u = X.mean(axis=0)
+    u /= np.linalg.norm(u)
+    along = X @ u
+    across = np.linalg.norm(X - np.outer(along, u), axis=1)
+    assert 0.59 < along.min() and along.max() < 1.01 and across.max() < 0.02
+    # eta * (lambda + |x|^2) < 1 on every row, so the contraction rate of the Check function leaves an interval
+    assert (w.eta * (w.lam + (w.dense.astype(np.float64) ** 2).sum(axis=1)) < 1).all()
+    again = wl.delay_servers(m=1024, d=256, k=8, n_lo=30, n_hi=90, tau=3)
+    assert np.array_equal(again.dense, w.dense) and np.array_equal(again.meta["w_start"], w.meta["w_start"])
+    b = wl.delay_servers(m=64, d=64, k=2, n_lo=3, n_hi=5, bf16=True)
+    assert b.dense.dtype == np.uint16 and b.is_bf16
