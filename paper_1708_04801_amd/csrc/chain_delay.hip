@@ -14,13 +14,14 @@
 // together with its squared length, which later tests need for the part across a sample,
 // |w|^2 - L^2/beta^2.  All arithmetic is fp64; the result is rounded to fp32 once, at the end.
 //
-// Three kernels.  delay_server_reg_kernel holds the ring in registers, newest iterate first, and shifts
+// Four kernels.  delay_server_reg_kernel holds the ring in registers, newest iterate first, and shifts
 // it when a candidate is accepted; the rows of the next samples (which do not depend on what is
 // accepted) are requested PF samples ahead, so a sample costs the pass over its row, one exchange of
 // sums and the decision.  It covers rows of up to 256 x EPT aligned elements and delays up to 4.
-// delay_server_batch_kernel is the same under the Check function, where nearly every sample is thrown
-// away: it decides B samples per exchange, rows staged in LDS.  delay_server_kernel keeps the ring in
-// the workspace and covers everything else.
+// For the same shapes, delay_server_batch_kernel decides B samples per exchange under the Check
+// function, where nearly every sample is thrown away, and delay_server_plain_kernel takes tau + 1 samples
+// per exchange without it, where the delay makes their gradients independent; both stage rows in LDS.
+// delay_server_kernel keeps the ring in the workspace and covers everything else.
 #include <atomic>
 
 #include "dense_rows.h"
@@ -448,6 +449,118 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayAr
     if (tid == 0) a.accepted[chain] = J;
 }
 
+// Rows on their way from HBM into LDS.  A ring of S row slots (sample s in slot s mod S), filled by loads
+// that land in LDS directly and need no registers while in flight; behind the slots, S pads that
+// receive the samples' labels the same way.  Every wave requests, and later reads back, only its own
+// part of a row (the columns its lanes own), so the slots need no barrier.  The compiler does not see
+// these loads; a wave's loads complete in issue order, so waiting until at most (S - B) samples' worth of
+// them are outstanding means the B oldest samples have landed.  Samples past the end of the stream are
+// requested all the same (the last valid row again), which keeps that count a constant.  A label goes
+// out before its row, so it has landed when the row has; fetched by an ordinary load inside the loop it
+// would queue behind the rows on their way and wait for all of them.
+template <typename TX, int EPT, int VEC, int S>
+struct LdsRows {
+    static constexpr int NT = kDelayThreads, NW = kDelayWaves;
+    using Frag = RowFrag<TX, NT, EPT, VEC>;
+    static_assert(VEC * sizeof(TX) == 16, "16-byte loads only");
+    static constexpr int CHUNKS = EPT / VEC;
+    static_assert(Frag::kWords == 4 * CHUNKS, "four words per chunk");
+    static constexpr uint32_t kWaveBytes = CHUNKS * kWave * 16;          // what one wave holds of one row
+    static constexpr uint32_t kSlotBytes = NW * kWaveBytes;
+    static constexpr uint32_t kLabelBytes = kWave * 4;                   // a wave's copy of one label (64 times)
+    static constexpr int kLoadsPerSample = CHUNKS + 1;                   // the row's chunks and its label
+    static constexpr size_t kBytes = (size_t)S * (kSlotBytes + NW * kLabelBytes);
+    typedef __attribute__((address_space(3))) uint32_t *lds_words;
+
+    lds_words stage;            // S slots, then S x NW label pads
+    uint32_t slot0, labels0;    // LDS byte addresses of this wave's part of slot 0 and of its pad 0
+    uint32_t voff, lane, wave;
+    u32x4 ry;                   // the labels as a buffer
+    const char *X;
+    int64_t row_stride, n;
+    uint32_t row_bytes;
+    RowWindow ahead;
+
+    // clears the slots (lanes whose columns lie beyond the row are out of the buffer's range: whether such
+    // a load writes zeros or nothing, the slots read as zero there afterwards); ends with a barrier
+    __device__ void init(lds_words lds, const DelayArgs &a, int chain, int64_t samples)
+    {
+        const int tid = threadIdx.x;
+        stage = lds;
+        lane = (uint32_t)(tid & (kWave - 1));
+        wave = (uint32_t)__builtin_amdgcn_readfirstlane(tid / kWave);
+        slot0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(size_t)lds + wave * kWaveBytes));
+        labels0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(size_t)lds + (uint32_t)S * kSlotBytes + wave * kLabelBytes));
+        voff = (uint32_t)(tid * 16);                 // this lane's bytes of chunk 0; chunk c adds c*NT*16
+        const uint64_t ybase = (uint64_t)(uintptr_t)a.y;
+        ry[0] = (uint32_t)ybase;
+        ry[1] = (uint32_t)(ybase >> 32) & 0xffffu;
+        ry[2] = (uint32_t)a.m * 4u;
+        ry[3] = 0x00020000u;
+        X = static_cast<const char *>(a.dense);
+        row_stride = a.ld * (int64_t)sizeof(TX);
+        row_bytes = (uint32_t)a.d * (uint32_t)sizeof(TX);
+        n = samples;
+        ahead.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
+        for (uint32_t i = (uint32_t)tid; i < (uint32_t)S * (kSlotBytes / 4); i += NT) stage[i] = 0u;
+        __syncthreads();
+    }
+    // the label and the row of sample s (of the last sample, beyond the end) into slot s mod S
+    __device__ void request(int64_t s)
+    {
+        const uint32_t row = ahead.get(s < n ? s : n - 1);
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                     :
+                     : "s"(labels0 + (uint32_t)(s % S) * (NW * kLabelBytes)), "v"(row * 4u), "s"(ry)
+                     : "memory", "m0");
+        const uint64_t base = (uint64_t)(uintptr_t)(X + (int64_t)row * row_stride);
+        u32x4 rx;
+        rx[0] = (uint32_t)base;
+        rx[1] = (uint32_t)(base >> 32) & 0xffffu;
+        rx[2] = row_bytes;
+        rx[3] = 0x00020000u;
+        const uint32_t slot = slot0 + (uint32_t)(s % S) * kSlotBytes;
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c)
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :
+                         : "s"(slot + c * (kWave * 16)), "v"(voff), "s"(rx), "s"(c * (NT * 16))
+                         : "memory", "m0");
+    }
+    // waits until the B oldest of the S samples requested last have landed
+    // (gfx9 encoding: vmcnt split over bits 3:0 and 15:14; expcnt and lgkmcnt left open)
+    template <int B>
+    __device__ static void wait_for_oldest()
+    {
+        constexpr int kLater = (S - B) * kLoadsPerSample;
+        static_assert(kLater >= 0 && kLater < 64, "the counter holds 63");
+        __builtin_amdgcn_s_waitcnt(((kLater & 0xF) | ((kLater >> 4) << 14)) | 0x0F70);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // this thread's elements of the row of sample s, and that sample's label
+    __device__ void take(int64_t s, Frag &x) const
+    {
+        const lds_words src = stage + (size_t)(s % S) * (kSlotBytes / 4) + (size_t)wave * (kWaveBytes / 4) + lane * 4;
+        typedef __attribute__((address_space(3))) const u32x4 *lds_quads;
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) {
+            const u32x4 q = *(lds_quads)(src + c * (kWave * 4));
+            x.w[4 * c + 0] = q[0];
+            x.w[4 * c + 1] = q[1];
+            x.w[4 * c + 2] = q[2];
+            x.w[4 * c + 3] = q[3];
+        }
+    }
+    __device__ float label(int64_t s) const
+    {
+        return __uint_as_float(stage[(size_t)S * (kSlotBytes / 4) + (size_t)(s % S) * (NW * kLabelBytes / 4) + (size_t)wave * (kLabelBytes / 4) + lane]);
+    }
+    // every LDS read of a slot must have returned before the slot is requested again
+    __device__ static void reads_done() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+    // nothing may still be landing when the wave ends
+    __device__ static void drain() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+};
+
 // All tests of the Check function for one sample, from its scalars alone and without branches on the
 // data: L[i] = w_{J-i}.x for i < R1, L[R1] = x.x; n2[i] = |w_{J-i}|^2; yhat and g belong to w_{J-tau}.
 template <int R1>
@@ -481,28 +594,16 @@ __device__ inline bool window_passes(const double *L, const double (&n2)[R1], in
 // that sample's candidate is written and the samples behind it are looked at again, against the new ring,
 // as the next batch.
 //
-// Rows travel from HBM straight into a ring of S row slots in LDS (sample s in slot s mod S), loads that
-// need no registers while in flight: the rows of samples pos .. pos+S-1 are always there or on their way,
-// so a batch's rows were asked for at least S-B samples earlier, and the row of an accepted sample is
-// still in its slot when the candidate is formed.  Each wave reads back only what its own loads wrote,
-// so the slots need no barrier.  The compiler does not see these loads; the one wait they need is placed
-// by hand: a wave's loads complete in issue order, so "at most (S-B) samples' worth outstanding" means
-// the batch has landed.  Samples from n on are asked for all the same (their last valid row again) so
-// that this count is a constant.
+// Rows come through LdsRows: the rows of samples pos .. pos+S-1 are always in LDS or on their way, so a
+// batch's rows were asked for at least S-B samples earlier, and the row of an accepted sample is still in
+// its slot when the candidate is formed.
 template <typename TX, int EPT, int VEC, int R1, int B, int S>
 __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(DelayArgs a)
 {
     constexpr int NT = kDelayThreads, NW = kDelayWaves, NV = B * (R1 + 1);
-    using Frag = RowFrag<TX, NT, EPT, VEC>;
-    static_assert(VEC * sizeof(TX) == 16, "16-byte loads only");
-    constexpr int CHUNKS = EPT / VEC;
-    static_assert(Frag::kWords == 4 * CHUNKS, "four words per chunk");
-    constexpr uint32_t kWaveBytes = CHUNKS * kWave * 16;          // what one wave holds of one row
-    constexpr uint32_t kSlotBytes = NW * kWaveBytes;
-    constexpr int kLoadsPerSample = CHUNKS + 1;                   // the row's chunks and its label
-    static_assert((S - B) * kLoadsPerSample < 64, "the wait below counts up to 63 loads");
-    constexpr uint32_t kLabelBytes = kWave * 4;                   // a wave's copy of one sample's label (64 times)
-    extern __shared__ __attribute__((aligned(16))) uint32_t stage[];     // S slots of kSlotBytes, then S x NW label pads
+    using Rows = LdsRows<TX, EPT, VEC, S>;
+    using Frag = typename Rows::Frag;
+    extern __shared__ __attribute__((aligned(16))) uint32_t stage[];     // Rows::kBytes
     __shared__ double red[2][NW][NV];
 
     const int tid = threadIdx.x;
@@ -511,9 +612,6 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
     const int chain = blockIdx.x;
     const int64_t n = a.n_samples[chain];
     const uint32_t d = (uint32_t)a.d;
-    const char *X = static_cast<const char *>(a.dense);
-    const int64_t row_stride = a.ld * (int64_t)sizeof(TX);
-    const uint32_t row_bytes = d * (uint32_t)sizeof(TX);
     const double eta = a.eta, eta_lambda = a.eta * a.lambda;
     const bool no_delay = R1 == 2 && a.tau == 0;
     int parity = 0;
@@ -563,82 +661,22 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
         return;
     }
 
-    RowWindow ahead;
-    ahead.init(a.seed_lo, a.seed_hi, (uint32_t)chain, (uint32_t)a.m);
-    typedef __attribute__((address_space(3))) uint32_t *lds_ptr;
-    const uint32_t stage0 = (uint32_t)__builtin_amdgcn_readfirstlane(
-        (int)((uint32_t)(size_t)(lds_ptr)&stage[0] + (uint32_t)wave * kWaveBytes));
-    const uint32_t voff = (uint32_t)(tid * 16);                   // this lane's bytes of chunk 0; chunk c adds c*NT*16
-    const uint32_t labels0 = (uint32_t)__builtin_amdgcn_readfirstlane(
-        (int)((uint32_t)(size_t)(lds_ptr)&stage[0] + (uint32_t)S * kSlotBytes + (uint32_t)wave * kLabelBytes));
-    const uint32_t *label_pad = stage + (size_t)S * (kSlotBytes / 4) + (size_t)wave * (kLabelBytes / 4);
-    u32x4 ry;                                                     // the labels as a buffer
-    {
-        const uint64_t base = (uint64_t)(uintptr_t)a.y;
-        ry[0] = (uint32_t)base;
-        ry[1] = (uint32_t)(base >> 32) & 0xffffu;
-        ry[2] = (uint32_t)a.m * 4u;
-        ry[3] = 0x00020000u;
-    }
-    // the label and the row of sample s (of the last sample, beyond the end) into slot s mod S; the
-    // label goes first, so it has landed when the row has.  (A label fetched by an ordinary load inside
-    // the loop would queue behind the rows on their way and wait for all of them.)
-    auto request = [&](int64_t s) {
-        const uint32_t row = ahead.get(s < n ? s : n - 1);
-        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-                     :
-                     : "s"(labels0 + (uint32_t)(s % S) * (NW * kLabelBytes)), "v"(row * 4u), "s"(ry)
-                     : "memory", "m0");
-        const uint64_t base = (uint64_t)(uintptr_t)(X + (int64_t)row * row_stride);
-        u32x4 rx;
-        rx[0] = (uint32_t)base;
-        rx[1] = (uint32_t)(base >> 32) & 0xffffu;
-        rx[2] = row_bytes;
-        rx[3] = 0x00020000u;
-        const uint32_t slot = stage0 + (uint32_t)(s % S) * kSlotBytes;
-#pragma unroll
-        for (int c = 0; c < CHUNKS; ++c)
-            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                         :
-                         : "s"(slot + c * (kWave * 16)), "v"(voff), "s"(rx), "s"(c * (NT * 16))
-                         : "memory", "m0");
-    };
-    // this thread's elements of the row in slot `slot`
-    auto take = [&](uint32_t slot, Frag &x) {
-        const uint32_t *src = stage + (size_t)slot * (kSlotBytes / 4) + (size_t)wave * (kWaveBytes / 4) + lane * 4;
-#pragma unroll
-        for (int c = 0; c < CHUNKS; ++c) {
-            const u32x4 q = *reinterpret_cast<const u32x4 *>(src + c * (kWave * 4));
-            x.w[4 * c + 0] = q[0];
-            x.w[4 * c + 1] = q[1];
-            x.w[4 * c + 2] = q[2];
-            x.w[4 * c + 3] = q[3];
-        }
-    };
-
-    // Lanes whose columns lie beyond the row are out of the buffer's range: whether such a load writes
-    // zeros or nothing, the slots read as zero there once they have been cleared.
-    for (uint32_t i = (uint32_t)tid; i < (uint32_t)S * (kSlotBytes / 4); i += NT) stage[i] = 0u;
-    __syncthreads();
-    for (int64_t s = 0; s < S; ++s) request(s);
+    Rows rows;
+    rows.init((typename Rows::lds_words)&stage[0], a, chain, n);
+    for (int64_t s = 0; s < S; ++s) rows.request(s);
     int64_t J = 0, pos = 0;
     while (pos < n) {
-        // the rows of samples pos .. pos+B-1 have landed once at most (S-B)*CHUNKS loads are outstanding
-        // (gfx9 encoding: vmcnt split over bits 3:0 and 15:14; expcnt and lgkmcnt left open)
-        constexpr int kLater = (S - B) * kLoadsPerSample;
-        __builtin_amdgcn_s_waitcnt(((kLater & 0xF) | ((kLater >> 4) << 14)) | 0x0F70);
-        __builtin_amdgcn_sched_barrier(0);
+        Rows::template wait_for_oldest<B>();        // samples pos .. pos+B-1 have landed
         double y[B];
 #pragma unroll
-        for (int b = 0; b < B; ++b)
-            y[b] = (double)__uint_as_float(label_pad[(size_t)((pos + b) % S) * (NW * kLabelBytes / 4) + lane]);
+        for (int b = 0; b < B; ++b) y[b] = (double)rows.label(pos + b);
         double v[NV];                               // v[b*(R1+1) + i] = w_{J-i}.x_b, i = R1: x_b.x_b
 #pragma unroll
         for (int t = 0; t < NV; ++t) v[t] = 0.0;
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             Frag x;
-            take((uint32_t)((pos + b) % S), x);
+            rows.take(pos + b, x);
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
                 const double xe = (double)x.at(e);
@@ -675,7 +713,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
             for (int b = 0; b < B; ++b)
                 if (b == taken) eg = eta * slope[b];
             Frag x;
-            take((uint32_t)((pos + taken) % S), x);
+            rows.take(pos + taken, x);
             double u2[1] = {0.0};
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
@@ -694,13 +732,13 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
             advance = taken + 1;
         }
         // the slots of the samples left behind take the rows that follow the ones on their way
-        __builtin_amdgcn_s_waitcnt(0xC07F);         // (every LDS read of those slots has returned)
+        Rows::reads_done();
 #pragma unroll
         for (int i = 0; i < B; ++i)
-            if (i < advance) request(pos + S + i);
+            if (i < advance) rows.request(pos + S + i);
         pos += advance;
     }
-    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");           // nothing may still be landing when the wave ends
+    Rows::drain();
 
     float *out = a.W + (int64_t)chain * a.d;
 #pragma unroll
@@ -709,6 +747,125 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
         if (col < d) out[col] = (float)r[0][e];
     }
     if (tid == 0) a.accepted[chain] = J;
+}
+
+// f(integral_constant<int, 0>) .. f(integral_constant<int, N-1>): a loop whose index is a constant
+// expression in its body (register arrays indexed through it are never indexed at run time).
+template <int N, typename F, int I = 0>
+__device__ inline void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, F, I + 1>(static_cast<F &&>(f));
+    }
+}
+
+// Without the Check function every sample is an update, and the delay itself gives the parallelism: the
+// gradients of the next tau + 1 samples are taken at w_{J-tau} .. w_J, which all exist already.  One
+// batch is R1 = tau + 1 samples: R1 projections (sample i on the iterate tau - i back) cross the workgroup
+// in one exchange, then R1 updates follow, element by element, with no further exchange.  The ring holds
+// exactly R1 iterates, so an update overwrites the oldest one - the very iterate its gradient was taken
+// at - and after a whole batch every iterate is back in the registers it started in: slot (i + 1) mod R1
+// is both where sample i's gradient is taken and where w_{J+i+1} goes; no register is ever moved.  (Slots
+// start as w_0, which is what an iterate before the start means.)  Rows come through LdsRows.
+template <typename TX, int EPT, int VEC, int R1, int S>
+__global__ __launch_bounds__(kDelayThreads) void delay_server_plain_kernel(DelayArgs a)
+{
+    constexpr int NT = kDelayThreads, NW = kDelayWaves, B = R1;
+    static_assert(R1 >= 2, "a delay of at least one");
+    using Rows = LdsRows<TX, EPT, VEC, S>;
+    using Frag = typename Rows::Frag;
+    extern __shared__ __attribute__((aligned(16))) uint32_t stage[];     // Rows::kBytes
+    __shared__ double red[2][NW][B];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int chain = blockIdx.x;
+    const int64_t n = a.n_samples[chain];
+    const uint32_t d = (uint32_t)a.d;
+    const double eta = a.eta, eta_lambda = a.eta * a.lambda;
+    int parity = 0;
+    auto column = [&](int e) { return (uint32_t)(((e / VEC) * NT + tid) * VEC + e % VEC); };
+
+    double r[R1][EPT];                              // r[p]: the iterate w_t with t mod R1 = p (w_0 before that)
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const uint32_t col = column(e);
+        const double w = (a.w_start && col < d) ? (double)a.w_start[col] : 0.0;
+#pragma unroll
+        for (int p = 0; p < R1; ++p) r[p][e] = w;
+    }
+    int newest = 0;                                 // slot of w_J when the loop ends
+    if (n > 0) {
+        Rows rows;
+        rows.init((typename Rows::lds_words)&stage[0], a, chain, n);
+        for (int64_t s = 0; s < S; ++s) rows.request(s);
+        for (int64_t pos = 0; pos < n; pos += B) {  // J = pos is a multiple of R1 here: w_J sits in slot 0
+            Rows::template wait_for_oldest<B>();
+            double y[B], v[B];
+            Frag x[B];
+            static_for<B>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                y[i] = (double)rows.label(pos + i);
+                rows.take(pos + i, x[i]);
+                v[i] = 0.0;
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) v[i] += r[(i + 1) % R1][e] * (double)x[i].at(e);
+            });
+            wave_sums_lane63(v, B);
+#pragma unroll
+            for (int i = 0; i < B; ++i)
+                if (lane == kWave - 1) red[parity][wave][i] = v[i];
+            __syncthreads();
+            double eg[B];
+            if (a.loss == kLossHinge) {
+#pragma unroll
+                for (int i = 0; i < B; ++i) {
+                    double sum = red[parity][0][i];
+#pragma unroll
+                    for (int w = 1; w < NW; ++w) sum += red[parity][w][i];
+                    eg[i] = eta * loss_slope<kLossHinge>(y[i], sum);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < B; ++i) {
+                    double sum = red[parity][0][i];
+#pragma unroll
+                    for (int w = 1; w < NW; ++w) sum += red[parity][w][i];
+                    eg[i] = eta * loss_slope<kLossLogistic>(y[i], sum);
+                }
+            }
+            parity ^= 1;
+            // w_{J+i+1} = w_{J+i} - eta*lambda*w_{J+i-tau} - eta*u*x_i, for the samples that exist
+            static_for<B>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                if (pos + i < n) {
+#pragma unroll
+                    for (int e = 0; e < EPT; ++e)
+                        r[(i + 1) % R1][e] = r[i % R1][e] - eta_lambda * r[(i + 1) % R1][e] - eg[i] * (double)x[i].at(e);
+                    newest = (i + 1) % R1;
+                }
+            });
+            Rows::reads_done();
+#pragma unroll
+            for (int i = 0; i < B; ++i) rows.request(pos + S + i);
+        }
+        Rows::drain();
+    }
+
+    float *out = a.W + (int64_t)chain * a.d;
+    static_for<R1>([&](auto pc) {                   // (a branch per slot: the ring is never indexed at run time)
+        constexpr int p = decltype(pc)::value;
+        if (newest == p) {
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) {
+                const uint32_t col = column(e);
+                if (col < d) out[col] = (float)r[p][e];
+            }
+        }
+    });
+    if (tid == 0) a.accepted[chain] = n > 0 ? n : 0;
 }
 
 constexpr int kDelayRegMaxTau = 4;
@@ -721,7 +878,7 @@ template <typename TX, int EPT, int VEC, int R1>
 bool launch_batch(const DelayArgs &a, hipStream_t s)
 {
     auto kernel = delay_server_batch_kernel<TX, EPT, VEC, R1, kDelayBatch, kDelaySlots>;
-    constexpr size_t bytes = (size_t)kDelaySlots * kDelayWaves * ((EPT / VEC) * kWave * 16 + kWave * 4);
+    constexpr size_t bytes = LdsRows<TX, EPT, VEC, kDelaySlots>::kBytes;
     static std::atomic<int> allowed{0};             // 0 not asked yet, 1 granted, -1 refused (asking twice is harmless)
     int may = allowed.load(std::memory_order_relaxed);
     if (may == 0) {
@@ -735,6 +892,24 @@ bool launch_batch(const DelayArgs &a, hipStream_t s)
     return true;
 }
 
+template <typename TX, int EPT, int VEC, int R1>
+bool launch_plain(const DelayArgs &a, hipStream_t s)
+{
+    auto kernel = delay_server_plain_kernel<TX, EPT, VEC, R1, kDelaySlots>;
+    constexpr size_t bytes = LdsRows<TX, EPT, VEC, kDelaySlots>::kBytes;
+    static std::atomic<int> allowed{0};
+    int may = allowed.load(std::memory_order_relaxed);
+    if (may == 0) {
+        may = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)bytes) == hipSuccess ? 1 : -1;
+        if (may < 0) (void)hipGetLastError();
+        allowed.store(may, std::memory_order_relaxed);
+    }
+    if (may < 0) return false;
+    hipLaunchKernelGGL(kernel, dim3(a.k), dim3(kDelayThreads), bytes, s, a);
+    return true;
+}
+
 // Launches the register kernel if one is built for this shape; *done tells.
 template <typename TX, int VEC>
 hipError_t launch_reg(const DelayArgs &a, hipStream_t s, bool *done)
@@ -743,7 +918,9 @@ hipError_t launch_reg(const DelayArgs &a, hipStream_t s, bool *done)
     *done = true;
 #define WPSGD_DELAY_REG(EPT, R1)                                                                                 \
     if (a.d <= (int64_t)kDelayThreads * EPT && r1 == R1) {                                                       \
-        if (a.check && a.m < (1 << 30) && launch_batch<TX, EPT, VEC, R1>(a, s))                                                   \
+        if (a.check && a.m < (1 << 30) && launch_batch<TX, EPT, VEC, R1>(a, s))                                  \
+            return hipGetLastError();                                                                            \
+        else if (!a.check && a.tau >= 1 && a.m < (1 << 30) && launch_plain<TX, EPT, VEC, R1>(a, s))              \
             return hipGetLastError();                                                                            \
         else                                                                                                     \
             hipLaunchKernelGGL((delay_server_reg_kernel<TX, EPT, VEC, R1, kDelayAhead>), dim3(a.k), dim3(kDelayThreads), 0, s, a); \

@@ -58,9 +58,11 @@ def compare(Wg, acc_g, Wo, acc_o, gap, label, max_ties=0):
 
 @pytest.mark.parametrize("tau", [0, 1, 2, 3, 4, 7, 16])
 @pytest.mark.parametrize("loss", [wl.HINGE, wl.LOGISTIC])
-def test_plain_delay_sgd(tau, loss):
-    """check = 0: every candidate is kept.  Ragged width (scalar loads), idle server, zero start."""
-    w = wl.delay_servers(m=512, d=1003, k=5, n_lo=40, n_hi=90, tau=tau, loss=loss, spread=0.3, data_seed=50 + tau)
+@pytest.mark.parametrize("d", [1003, 1024, 2560])
+def test_plain_delay_sgd(tau, loss, d):
+    """check = 0: every candidate is kept.  Ragged width (scalar loads) and aligned widths (tau + 1 samples
+    per exchange for delays 1 to 4), sample counts that are no multiple of tau + 1, idle server, zero start."""
+    w = wl.delay_servers(m=512, d=d, k=5, n_lo=40, n_hi=90, tau=tau, loss=loss, spread=0.3, data_seed=50 + tau)
     w.n_steps[3] = 0
     Wg, acc_g, Wo, acc_o, gap = run_both(w, tau, check=False, start=(tau % 2 == 0))
     assert acc_g.tolist() == w.n_steps.tolist()
