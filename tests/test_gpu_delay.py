@@ -90,6 +90,21 @@ def test_servers_under_check_on_rows_of_the_measured_width(tau, d, bf16):
     compare(Wg, acc_g, Wo, acc_o, gap, f"plain tau={tau} d={d}")
 
 
+@pytest.mark.parametrize("tau", [0, 1, 2, 4])
+@pytest.mark.parametrize("d", [8, 64, 2048])
+def test_few_samples_and_narrow_rows(tau, d):
+    """Servers with 0 to 11 samples (less than a batch, one more than a batch, ...) on rows that fill only
+    a few lanes or every lane of the widest eight-element shape; one data row only for the last server's
+    stream to repeat."""
+    w = wl.delay_servers(m=96, d=d, k=12, n_lo=1, n_hi=2, tau=tau, spread=0.05, data_seed=200 + tau + d)
+    w.n_steps[:] = np.arange(12)
+    for check in (True, False):
+        Wg, acc_g, Wo, acc_o, gap = run_both(w, tau, check=check)
+        compare(Wg, acc_g, Wo, acc_o, gap, f"few samples tau={tau} d={d} check={check}", max_ties=2)
+    one = wl.delay_servers(m=1, d=d, k=3, n_lo=5, n_hi=9, tau=tau, data_seed=9)
+    compare(*run_both(one, tau, check=False), f"one row tau={tau} d={d}")
+
+
 def test_check_from_the_zero_start_of_algorithm_3():
     """From w_0 = 0 nothing lies across the second sample yet while w_1 does, so the second update passes
     only for a sample parallel to the first, and then the comparison of the two parts is a tie."""
