@@ -176,7 +176,8 @@ int wpsgd_chains_status(const void *workspace, void *stream);
  *   accepted     DEVICE out, k entries: J of each server.  Phase 2 of Algorithm 3 is wpsgd_weights_rate
  *                on these counts followed by wpsgd_combine.
  *   workspace    DEVICE scratch of at least wpsgd_run_delay_chains_workspace(X, k, tau) bytes (0 is
- *                returned for arguments the call would refuse), 256-byte aligned
+ *                returned for arguments the call would refuse), 256-byte aligned: the sample counts, room
+ *                for the servers' iterates, and 32 bytes per row of X for what the test needs of a row
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.                              */
 size_t wpsgd_run_delay_chains_workspace(const wpsgd_matrix *X, int k, int tau);
 int wpsgd_run_delay_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_samples,

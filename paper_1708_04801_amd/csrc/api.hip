@@ -582,10 +582,13 @@ static size_t delay_ring_bytes(const wpsgd_matrix *X, int k, int tau)
     return (size_t)k * (size_t)(std::max(tau, 1) + 2) * (size_t)X->d * sizeof(double);
 }
 
+// a table of 32 bytes per row: what the Check function needs of a row and not of the model
+static size_t delay_table_bytes(const wpsgd_matrix *X) { return align256((size_t)X->m * 32); }
+
 size_t wpsgd_run_delay_chains_workspace(const wpsgd_matrix *X, int k, int tau)
 {
     if (check_matrix(X) != WPSGD_OK || !X->dense || k < 1 || tau < 0 || tau > kDelayMaxTau) return 0;
-    return align256((size_t)k * sizeof(int64_t)) + align256(delay_ring_bytes(X, k, tau));
+    return align256((size_t)k * sizeof(int64_t)) + align256(delay_ring_bytes(X, k, tau)) + delay_table_bytes(X);
 }
 
 int wpsgd_run_delay_chains(const wpsgd_matrix *X, const float *y, int k, const int64_t *n_samples,
@@ -626,6 +629,13 @@ int wpsgd_run_delay_chains(const wpsgd_matrix *X, const float *y, int k, const i
     a.ring = reinterpret_cast<double *>(base + align256((size_t)k * sizeof(int64_t)));
     a.W = W;
     a.accepted = accepted;
+    // The row table costs a pass over the whole data set: it pays when the servers together visit a
+    // good part of the rows (the kernel that uses it is only chosen under the Check function).
+    int64_t visits = 0;
+    for (int i = 0; i < k; ++i) visits += std::min<int64_t>(n_samples[i], INT64_MAX / 2 / k);
+    a.row_table = (check != 0 && visits >= X->m / 4)
+                      ? base + align256((size_t)k * sizeof(int64_t)) + align256(delay_ring_bytes(X, k, tau))
+                      : nullptr;
     const bool start_ok = !w_start || (uintptr_t)w_start % 4 == 0;
     if (!start_ok) return WPSGD_INVALID_ARG;
     hipError_t e = launch_delay_servers(a, (int)X->dtype, dense_vec(X), s);

@@ -451,15 +451,17 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_reg_kernel(DelayAr
 
 // Rows on their way from HBM into LDS.  A ring of S row slots (sample s in slot s mod S), filled by loads
 // that land in LDS directly and need no registers while in flight; behind the slots, S pads that
-// receive the samples' labels the same way.  Every wave requests, and later reads back, only its own
+// receive, the same way, a small record per sample: SIDE dwords from an array indexed by the sample's
+// row (SIDE = 1: its label; SIDE = 8: its entry of the row table, see DelayRowEntry).  Every wave requests, and later reads back, only its own
 // part of a row (the columns its lanes own), so the slots need no barrier.  The compiler does not see
 // these loads; a wave's loads complete in issue order, so waiting until at most (S - B) samples' worth of
 // them are outstanding means the B oldest samples have landed.  Samples past the end of the stream are
-// requested all the same (the last valid row again), which keeps that count a constant.  A label goes
+// requested all the same (the last valid row again), which keeps that count a constant.  The record goes
 // out before its row, so it has landed when the row has; fetched by an ordinary load inside the loop it
 // would queue behind the rows on their way and wait for all of them.
-template <typename TX, int EPT, int VEC, int S>
+template <typename TX, int EPT, int VEC, int S, int SIDE>
 struct LdsRows {
+    static_assert(SIDE >= 1 && SIDE <= kWave && (SIDE & (SIDE - 1)) == 0, "a power of two of dwords");
     static constexpr int NT = kDelayThreads, NW = kDelayWaves;
     using Frag = RowFrag<TX, NT, EPT, VEC>;
     static_assert(VEC * sizeof(TX) == 16, "16-byte loads only");
@@ -467,15 +469,15 @@ struct LdsRows {
     static_assert(Frag::kWords == 4 * CHUNKS, "four words per chunk");
     static constexpr uint32_t kWaveBytes = CHUNKS * kWave * 16;          // what one wave holds of one row
     static constexpr uint32_t kSlotBytes = NW * kWaveBytes;
-    static constexpr uint32_t kLabelBytes = kWave * 4;                   // a wave's copy of one label (64 times)
-    static constexpr int kLoadsPerSample = CHUNKS + 1;                   // the row's chunks and its label
+    static constexpr uint32_t kLabelBytes = kWave * 4;                   // a wave's copy of one record (64 / SIDE times)
+    static constexpr int kLoadsPerSample = CHUNKS + 1;                   // the row's chunks and its record
     static constexpr size_t kBytes = (size_t)S * (kSlotBytes + NW * kLabelBytes);
     typedef __attribute__((address_space(3))) uint32_t *lds_words;
 
-    lds_words stage;            // S slots, then S x NW label pads
+    lds_words stage;            // S slots, then S x NW record pads
     uint32_t slot0, labels0;    // LDS byte addresses of this wave's part of slot 0 and of its pad 0
-    uint32_t voff, lane, wave;
-    u32x4 ry;                   // the labels as a buffer
+    uint32_t voff, lane, wave, side_lane;
+    u32x4 ry;                   // the records as a buffer
     const char *X;
     int64_t row_stride, n;
     uint32_t row_bytes;
@@ -483,7 +485,7 @@ struct LdsRows {
 
     // clears the slots (lanes whose columns lie beyond the row are out of the buffer's range: whether such
     // a load writes zeros or nothing, the slots read as zero there afterwards); ends with a barrier
-    __device__ void init(lds_words lds, const DelayArgs &a, int chain, int64_t samples)
+    __device__ void init(lds_words lds, const DelayArgs &a, int chain, int64_t samples, const void *records)
     {
         const int tid = threadIdx.x;
         stage = lds;
@@ -492,11 +494,12 @@ struct LdsRows {
         slot0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(size_t)lds + wave * kWaveBytes));
         labels0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(size_t)lds + (uint32_t)S * kSlotBytes + wave * kLabelBytes));
         voff = (uint32_t)(tid * 16);                 // this lane's bytes of chunk 0; chunk c adds c*NT*16
-        const uint64_t ybase = (uint64_t)(uintptr_t)a.y;
+        const uint64_t ybase = (uint64_t)(uintptr_t)records;
         ry[0] = (uint32_t)ybase;
         ry[1] = (uint32_t)(ybase >> 32) & 0xffffu;
-        ry[2] = (uint32_t)a.m * 4u;
+        ry[2] = (uint32_t)a.m * (uint32_t)(SIDE * 4);
         ry[3] = 0x00020000u;
+        side_lane = (lane & (uint32_t)(SIDE - 1)) * 4u;
         X = static_cast<const char *>(a.dense);
         row_stride = a.ld * (int64_t)sizeof(TX);
         row_bytes = (uint32_t)a.d * (uint32_t)sizeof(TX);
@@ -505,13 +508,13 @@ struct LdsRows {
         for (uint32_t i = (uint32_t)tid; i < (uint32_t)S * (kSlotBytes / 4); i += NT) stage[i] = 0u;
         __syncthreads();
     }
-    // the label and the row of sample s (of the last sample, beyond the end) into slot s mod S
+    // the record and the row of sample s (of the last sample, beyond the end) into slot s mod S
     __device__ void request(int64_t s)
     {
         const uint32_t row = ahead.get(s < n ? s : n - 1);
         asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                      :
-                     : "s"(labels0 + (uint32_t)(s % S) * (NW * kLabelBytes)), "v"(row * 4u), "s"(ry)
+                     : "s"(labels0 + (uint32_t)(s % S) * (NW * kLabelBytes)), "v"(row * (uint32_t)(SIDE * 4) + side_lane), "s"(ry)
                      : "memory", "m0");
         const uint64_t base = (uint64_t)(uintptr_t)(X + (int64_t)row * row_stride);
         u32x4 rx;
@@ -537,7 +540,7 @@ struct LdsRows {
         __builtin_amdgcn_s_waitcnt(((kLater & 0xF) | ((kLater >> 4) << 14)) | 0x0F70);
         __builtin_amdgcn_sched_barrier(0);
     }
-    // this thread's elements of the row of sample s, and that sample's label
+    // this thread's elements of the row of sample s
     __device__ void take(int64_t s, Frag &x) const
     {
         const lds_words src = stage + (size_t)(s % S) * (kSlotBytes / 4) + (size_t)wave * (kWaveBytes / 4) + lane * 4;
@@ -551,9 +554,14 @@ struct LdsRows {
             x.w[4 * c + 3] = q[3];
         }
     }
-    __device__ float label(int64_t s) const
+    // dword j of sample s's record (the same address in every lane)
+    __device__ uint32_t side(int64_t s, int j) const
     {
-        return __uint_as_float(stage[(size_t)S * (kSlotBytes / 4) + (size_t)(s % S) * (NW * kLabelBytes / 4) + (size_t)wave * (kLabelBytes / 4) + lane]);
+        return stage[(size_t)S * (kSlotBytes / 4) + (size_t)(s % S) * (NW * kLabelBytes / 4) + (size_t)wave * (kLabelBytes / 4) + j];
+    }
+    __device__ double side_f64(int64_t s, int j) const
+    {
+        return __longlong_as_double((long long)(((uint64_t)side(s, j + 1) << 32) | side(s, j)));
     }
     // every LDS read of a slot must have returned before the slot is requested again
     __device__ static void reads_done() { __builtin_amdgcn_s_waitcnt(0xC07F); }
@@ -561,15 +569,51 @@ struct LdsRows {
     __device__ static void drain() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 };
 
+// What the Check function needs of a row and not of the model: computed once per row of the data set
+// instead of once per visit.  32 bytes, read as eight dwords.
+struct DelayRowEntry {
+    double beta2;       // x.x
+    double rate;        // (eta*lambda + eta*beta2)^(1/reach)
+    float y;            // the label
+    float pad[3];
+};
+static_assert(sizeof(DelayRowEntry) == 32, "eight dwords");
+
+template <typename TX, int VEC>
+__global__ __launch_bounds__(kDelayThreads) void delay_row_table_kernel(DelayArgs a, DelayRowEntry *table, int reach)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = (int64_t)blockIdx.x * kDelayWaves + threadIdx.x / kWave;       // one wave per row
+    if (row >= a.m) return;
+    const TX *xr = static_cast<const TX *>(a.dense) + row * a.ld;
+    double acc = 0.0;
+    for (int64_t col = (int64_t)lane * VEC; col < a.d; col += (int64_t)kWave * VEC) {
+        DelayRow<TX, VEC> c;
+        c.load(xr + col);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc += c.x[j] * c.x[j];
+    }
+    const double beta2 = wave_sum(acc);
+    if (lane == 0) {
+        const double base = a.eta * a.lambda + a.eta * beta2;
+        DelayRowEntry e;
+        e.beta2 = beta2;
+        e.rate = reach == 1 ? base : reach == 2 ? delay_root<2>(base) : reach == 3 ? delay_root<3>(base) : delay_root<4>(base);
+        e.y = a.y[row];
+        e.pad[0] = e.pad[1] = e.pad[2] = 0.0f;
+        table[row] = e;
+    }
+}
+
 // All tests of the Check function for one sample, from its scalars alone and without branches on the
-// data: L[i] = w_{J-i}.x for i < R1, L[R1] = x.x; n2[i] = |w_{J-i}|^2; yhat and g belong to w_{J-tau}.
+// data: L[i] = w_{J-i}.x; n2[i] = |w_{J-i}|^2; beta2 = x.x and rate from the row table; yhat and g
+// belong to w_{J-tau}.
 template <int R1>
-__device__ inline bool window_passes(const double *L, const double (&n2)[R1], int64_t J, double eta, double eta_lambda,
-                                     double yhat, double g)
+__device__ inline bool window_passes(const double *L, const double (&n2)[R1], double beta2, double rate, int64_t J,
+                                     double eta, double eta_lambda, double yhat, double g)
 {
     // (bitwise and/or on purpose: nothing here is worth a branch, and without branches the tests of
     // several samples can be interleaved)
-    const double beta2 = L[R1];
     bool ok = true;
 #pragma unroll
     for (int i = 0; i + 1 < R1; ++i) {          // pairs (w_{J-i-1}, w_{J-i}) that some triple holds
@@ -577,7 +621,6 @@ __device__ inline bool window_passes(const double *L, const double (&n2)[R1], in
         const bool plain = !(n2[i] > n2[i + 1]);
         ok = ok & ((J < i + 1) | (beta2 > 0.0 ? along : plain));
     }
-    const double rate = delay_root<R1 - 1>(eta_lambda + eta * beta2);
     ok = ok & ((rate < 1.0) | (J == 0));        // with no triple to test nothing is rejected
 #pragma unroll
     for (int i = 0; i + 2 < R1; ++i) ok = ok & ((J < i + 2) | inside_interval(L[i + 2], L[i + 1], L[i], rate));
@@ -588,7 +631,7 @@ __device__ inline bool window_passes(const double *L, const double (&n2)[R1], in
 
 // Under the Check function nearly every sample is thrown away, and a sample that is thrown away leaves
 // the ring as it was.  This kernel therefore looks at B samples at once: it projects the ring on all B
-// rows, exchanges the B x (R1 + 1) sums in one round and takes the B decisions side by side in
+// rows, exchanges the B x R1 sums in one round and takes the B decisions side by side in
 // straight-line code (so that their dependent fp64 chains overlap), each as if the samples before it had
 // been rejected.  The decisions up to and including the first acceptance are then the sequential ones;
 // that sample's candidate is written and the samples behind it are looked at again, against the new ring,
@@ -600,8 +643,8 @@ __device__ inline bool window_passes(const double *L, const double (&n2)[R1], in
 template <typename TX, int EPT, int VEC, int R1, int B, int S>
 __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(DelayArgs a)
 {
-    constexpr int NT = kDelayThreads, NW = kDelayWaves, NV = B * (R1 + 1);
-    using Rows = LdsRows<TX, EPT, VEC, S>;
+    constexpr int NT = kDelayThreads, NW = kDelayWaves, NV = B * R1;
+    using Rows = LdsRows<TX, EPT, VEC, S, 8>;       // with each row its entry of the row table
     using Frag = typename Rows::Frag;
     extern __shared__ __attribute__((aligned(16))) uint32_t stage[];     // Rows::kBytes
     __shared__ double red[2][NW][NV];
@@ -662,15 +705,19 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
     }
 
     Rows rows;
-    rows.init((typename Rows::lds_words)&stage[0], a, chain, n);
+    rows.init((typename Rows::lds_words)&stage[0], a, chain, n, a.row_table);
     for (int64_t s = 0; s < S; ++s) rows.request(s);
     int64_t J = 0, pos = 0;
     while (pos < n) {
         Rows::template wait_for_oldest<B>();        // samples pos .. pos+B-1 have landed
-        double y[B];
+        double y[B], beta2[B], rate[B];             // DelayRowEntry of each sample's row
 #pragma unroll
-        for (int b = 0; b < B; ++b) y[b] = (double)rows.label(pos + b);
-        double v[NV];                               // v[b*(R1+1) + i] = w_{J-i}.x_b, i = R1: x_b.x_b
+        for (int b = 0; b < B; ++b) {
+            beta2[b] = rows.side_f64(pos + b, 0);
+            rate[b] = rows.side_f64(pos + b, 2);
+            y[b] = (double)__uint_as_float(rows.side(pos + b, 4));
+        }
+        double v[NV];                               // v[b*R1 + i] = w_{J-i}.x_b
 #pragma unroll
         for (int t = 0; t < NV; ++t) v[t] = 0.0;
 #pragma unroll
@@ -680,9 +727,8 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
 #pragma unroll
             for (int e = 0; e < EPT; ++e) {
                 const double xe = (double)x.at(e);
-                v[b * (R1 + 1) + R1] += xe * xe;
 #pragma unroll
-                for (int i = 0; i < R1; ++i) v[b * (R1 + 1) + i] += r[i][e] * xe;
+                for (int i = 0; i < R1; ++i) v[b * R1 + i] += r[i][e] * xe;
             }
         }
         block_sums(v, std::integral_constant<int, NV>{});
@@ -690,7 +736,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
         bool keep[B];
         double slope[B], yhat[B];
 #pragma unroll
-        for (int b = 0; b < B; ++b) yhat[b] = no_delay ? v[b * (R1 + 1)] : v[b * (R1 + 1) + R1 - 1];
+        for (int b = 0; b < B; ++b) yhat[b] = no_delay ? v[b * R1] : v[b * R1 + R1 - 1];
         if (a.loss == kLossHinge) {                 // (one branch for the batch, so that the B slopes share a block)
 #pragma unroll
             for (int b = 0; b < B; ++b) slope[b] = loss_slope<kLossHinge>(y[b], yhat[b]);
@@ -700,7 +746,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_batch_kernel(Delay
         }
 #pragma unroll
         for (int b = 0; b < B; ++b)
-            keep[b] = (pos + b < n) & window_passes<R1>(v + b * (R1 + 1), n2, J, eta, eta_lambda, yhat[b], slope[b]);
+            keep[b] = (pos + b < n) & window_passes<R1>(v + b * R1, n2, beta2[b], rate[b], J, eta, eta_lambda, yhat[b], slope[b]);
         int taken = B;                              // the first sample of the batch that is accepted
 #pragma unroll
         for (int b = B - 1; b >= 0; --b) taken = keep[b] ? b : taken;
@@ -773,7 +819,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_plain_kernel(Delay
 {
     constexpr int NT = kDelayThreads, NW = kDelayWaves, B = R1;
     static_assert(R1 >= 2, "a delay of at least one");
-    using Rows = LdsRows<TX, EPT, VEC, S>;
+    using Rows = LdsRows<TX, EPT, VEC, S, 1>;       // with each row its label
     using Frag = typename Rows::Frag;
     extern __shared__ __attribute__((aligned(16))) uint32_t stage[];     // Rows::kBytes
     __shared__ double red[2][NW][B];
@@ -799,7 +845,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_plain_kernel(Delay
     int newest = 0;                                 // slot of w_J when the loop ends
     if (n > 0) {
         Rows rows;
-        rows.init((typename Rows::lds_words)&stage[0], a, chain, n);
+        rows.init((typename Rows::lds_words)&stage[0], a, chain, n, a.y);
         for (int64_t s = 0; s < S; ++s) rows.request(s);
         for (int64_t pos = 0; pos < n; pos += B) {  // J = pos is a multiple of R1 here: w_J sits in slot 0
             Rows::template wait_for_oldest<B>();
@@ -807,7 +853,7 @@ __global__ __launch_bounds__(kDelayThreads) void delay_server_plain_kernel(Delay
             Frag x[B];
             static_for<B>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
-                y[i] = (double)rows.label(pos + i);
+                y[i] = (double)__uint_as_float(rows.side(pos + i, 0));
                 rows.take(pos + i, x[i]);
                 v[i] = 0.0;
 #pragma unroll
@@ -878,7 +924,7 @@ template <typename TX, int EPT, int VEC, int R1>
 bool launch_batch(const DelayArgs &a, hipStream_t s)
 {
     auto kernel = delay_server_batch_kernel<TX, EPT, VEC, R1, kDelayBatch, kDelaySlots>;
-    constexpr size_t bytes = LdsRows<TX, EPT, VEC, kDelaySlots>::kBytes;
+    constexpr size_t bytes = LdsRows<TX, EPT, VEC, kDelaySlots, 8>::kBytes;
     static std::atomic<int> allowed{0};             // 0 not asked yet, 1 granted, -1 refused (asking twice is harmless)
     int may = allowed.load(std::memory_order_relaxed);
     if (may == 0) {
@@ -888,6 +934,9 @@ bool launch_batch(const DelayArgs &a, hipStream_t s)
         allowed.store(may, std::memory_order_relaxed);
     }
     if (may < 0) return false;                      // the per-sample kernel serves instead
+    // what depends on a row alone, once per row
+    hipLaunchKernelGGL((delay_row_table_kernel<TX, VEC>), dim3((unsigned)((a.m + kDelayWaves - 1) / kDelayWaves)), dim3(kDelayThreads),
+                       0, s, a, static_cast<DelayRowEntry *>(a.row_table), R1 - 1);
     hipLaunchKernelGGL(kernel, dim3(a.k), dim3(kDelayThreads), bytes, s, a);
     return true;
 }
@@ -896,7 +945,7 @@ template <typename TX, int EPT, int VEC, int R1>
 bool launch_plain(const DelayArgs &a, hipStream_t s)
 {
     auto kernel = delay_server_plain_kernel<TX, EPT, VEC, R1, kDelaySlots>;
-    constexpr size_t bytes = LdsRows<TX, EPT, VEC, kDelaySlots>::kBytes;
+    constexpr size_t bytes = LdsRows<TX, EPT, VEC, kDelaySlots, 1>::kBytes;
     static std::atomic<int> allowed{0};
     int may = allowed.load(std::memory_order_relaxed);
     if (may == 0) {
@@ -918,7 +967,7 @@ hipError_t launch_reg(const DelayArgs &a, hipStream_t s, bool *done)
     *done = true;
 #define WPSGD_DELAY_REG(EPT, R1)                                                                                 \
     if (a.d <= (int64_t)kDelayThreads * EPT && r1 == R1) {                                                       \
-        if (a.check && a.m < (1 << 30) && launch_batch<TX, EPT, VEC, R1>(a, s))                                  \
+        if (a.check && a.row_table && a.m < (1 << 27) && launch_batch<TX, EPT, VEC, R1>(a, s))                   \
             return hipGetLastError();                                                                            \
         else if (!a.check && a.tau >= 1 && a.m < (1 << 30) && launch_plain<TX, EPT, VEC, R1>(a, s))              \
             return hipGetLastError();                                                                            \

@@ -67,6 +67,8 @@ struct DelayArgs {
     int loss, tau, check;
     uint32_t seed_lo, seed_hi;
     double *ring;             // DEVICE, k x (max(tau,1)+2) x d: the iterates each server keeps
+    void *row_table;          // DEVICE, m x 32 bytes: room for what the Check function needs of each row, or
+                              // NULL when the servers visit too few rows for such a table to pay
     float *W;                 // k x d out
     int64_t *accepted;        // k out: updates each server has made
 };

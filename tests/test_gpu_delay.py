@@ -105,6 +105,17 @@ def test_few_samples_and_narrow_rows(tau, d):
     compare(*run_both(one, tau, check=False), f"one row tau={tau} d={d}")
 
 
+@pytest.mark.parametrize("tau", [0, 2, 4])
+def test_servers_that_visit_few_of_many_rows(tau):
+    """When the servers together visit less than a quarter of the rows, no table of per-row quantities is
+    built and every sample is decided on its own (another kernel than in the cases above)."""
+    w = wl.delay_servers(m=16384, d=1024, k=3, n_lo=300, n_hi=900, tau=tau, data_seed=70 + tau)
+    assert 4 * w.n_steps.sum() < w.m
+    Wg, acc_g, Wo, acc_o, gap = run_both(w, tau, check=True)
+    compare(Wg, acc_g, Wo, acc_o, gap, f"few visits tau={tau}", max_ties=1)
+    assert acc_o.max() >= 4
+
+
 def test_check_from_the_zero_start_of_algorithm_3():
     """From w_0 = 0 nothing lies across the second sample yet while w_1 does, so the second update passes
     only for a sample parallel to the first, and then the comparison of the two parts is a tie."""
@@ -185,5 +196,5 @@ def test_refusals():
                                    0.1, 0.1, wl.HINGE, 0, 2,
                                    workspace=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
     assert e.value.status == api.UNSUPPORTED
-    assert api.wpsgd_run_delay_chains_workspace(X, 2, 2) == 256 + 2 * 4 * 32 * 8
+    assert api.wpsgd_run_delay_chains_workspace(X, 2, 2) == 256 + 2 * 4 * 32 * 8 + 64 * 32
     assert api.wpsgd_run_delay_chains_workspace(X, 2, 17) == 0

@@ -193,10 +193,11 @@ def test_workspace_sizes():
     ws = api.wpsgd_run_chains_workspace(_FakeMatrix(1000, 1 << 20, csr=True), 128, api.LOGISTIC)
     assert 128 * (1 << 20) * 4 <= ws < 128 * (1 << 20) * 4 + 4096 + 4 * 1000 + 2048 + 1024 + 256
     assert api.wpsgd_combine_workspace(64, 4096) == 512
-    # delay servers: the sample counts, then max(tau, 1) + 2 vectors of d doubles per server
-    assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 64), 4, 0) == 256 + 4 * 3 * 64 * 8
-    assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 64), 4, 1) == 256 + 4 * 3 * 64 * 8
-    assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 100), 40, 16) == 512 + 40 * 18 * 100 * 8
+    # delay servers: the sample counts, then max(tau, 1) + 2 vectors of d doubles per server, then 32 bytes per row
+    assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 64), 4, 0) == 256 + 4 * 3 * 64 * 8 + 4096 * 32
+    assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 64), 4, 1) == 256 + 4 * 3 * 64 * 8 + 4096 * 32
+    assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 100), 40, 16) == 512 + 40 * 18 * 100 * 8 + 4096 * 32
+    assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(3, 64), 1, 2) == 256 + 4 * 64 * 8 + 256
     # what the call would refuse has no size: a negative or too long delay, no servers, sparse rows
     assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 64), 4, -1) == 0
     assert api.wpsgd_run_delay_chains_workspace(_FakeMatrix(4096, 64), 4, 17) == 0
